@@ -1,0 +1,137 @@
+/*
+ * m2rnn.h -- C ABI of the MI355X (gfx950) M2RNN recurrent-scan library.
+ *
+ * The library computes, for every batch element b and head n independently,
+ * the matrix-state recurrence of the paper's "M2RNN layer" section
+ * (recurrence equations; forward Algorithm 1, backward Algorithm 2):
+ *
+ *     Z_t = tanh(H_{t-1} W_n + k_t v_t^T)        H in R^{K x V}, W_n in R^{V x V}
+ *     H_t = f_t H_{t-1} + (1 - f_t) Z_t          f_t in [0,1], one scalar per (b,t,n)
+ *     y_t = H_t^T q_t                            (the w_r (.) v_t residual of the
+ *                                                 y equation is left to the caller,
+ *                                                 as in Algorithm 1)
+ *
+ * and its exact back-propagation through time.  Every step runs in hand-written
+ * HIP kernels; there is no CPU path.
+ *
+ * General rules for every entry point
+ *   - All tensor pointers are DEVICE pointers on the current HIP device, dense,
+ *     row-major in the shape given, 16-byte aligned.  The descriptor is a HOST
+ *     pointer.  The caller owns every buffer; the library allocates nothing,
+ *     frees nothing, and keeps no pointer after the call returns.
+ *   - Inputs are read-only.  Outputs are overwritten (never accumulated into),
+ *     so they need no initialisation.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and the call returns without synchronising.
+ *   - Every failure is a return code; nothing aborts or throws.  Validation
+ *     happens on the host before anything is launched, so a failed call has
+ *     launched nothing and written nothing.
+ *   - Results are bit-reproducible: all cross-workgroup sums (over state rows,
+ *     over heads that share q/k, over the batch for dW) are done in a fixed
+ *     order, without atomics (the paper's Algorithm 2 uses atomic adds).
+ */
+#ifndef M2RNN_H_
+#define M2RNN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  M2RNN_OK = 0,
+  M2RNN_ERR_NULL = 1,      /* a required pointer is NULL                            */
+  M2RNN_ERR_SHAPE = 2,     /* a dimension is out of the supported set               */
+  M2RNN_ERR_DTYPE = 3,     /* desc.io is not a known dtype                          */
+  M2RNN_ERR_ALIGN = 4,     /* a pointer is not 16-byte aligned                      */
+  M2RNN_ERR_WORKSPACE = 5, /* workspace_bytes < m2rnn_workspace_bytes()             */
+  M2RNN_ERR_HIP = 6,       /* a HIP call (launch, attribute) failed                 */
+  M2RNN_ERR_CHUNK = 7      /* desc.chunk is outside [0, m2rnn_max_chunk()]          */
+} m2rnn_status;
+
+typedef enum {
+  M2RNN_F32 = 0, /* q,k,v,W,y,dy,dq,dk,dv are float32; contraction in fp32          */
+  M2RNN_BF16 = 1 /* they are bfloat16; the state stays fp32, the contractions run
+                    on the matrix cores with fp16 operands and fp32 accumulation   */
+} m2rnn_dtype;
+
+/* Problem descriptor (host memory).  Zero-initialise, then fill. */
+typedef struct {
+  int32_t B;   /* batch size, >= 0                                                  */
+  int32_t T;   /* time steps, >= 0 (T == 0: HT = H0, dH0 = dHT, dW = 0)              */
+  int32_t N;   /* heads of v, f, W, y (paper: N_v = N_f = N_w = N), >= 1            */
+  int32_t Nqk; /* heads of q and k: N (one per head) or a divisor of N; head n
+                  reads q/k head n / (N / Nqk).  Nqk = 1 is the paper's
+                  multi-value form (Algorithm 1's Q, K in R^{BTK}).                 */
+  int32_t K;   /* state rows    (paper: multiples of 16); one of 16, 32, 64, 128    */
+  int32_t V;   /* state columns (paper: multiples of 16); one of 16, 32, 64, 128    */
+  int32_t io;  /* m2rnn_dtype of q,k,v,W,y,dy,dq,dk,dv                               */
+  int32_t chunk; /* checkpoint interval C in steps; 0 = m2rnn_default_chunk()        */
+  uint32_t flags; /* reserved, must be 0                                             */
+} m2rnn_desc;
+
+/* Human-readable name of a status code (static storage). */
+const char *m2rnn_status_string(m2rnn_status s);
+
+/* Checkpoint interval the library picks when desc.chunk == 0, and the largest
+ * one it accepts, for this shape and dtype (0 if the descriptor is invalid). */
+int32_t m2rnn_default_chunk(const m2rnn_desc *desc);
+int32_t m2rnn_max_chunk(const m2rnn_desc *desc);
+
+/* Bytes of the checkpoint buffer: fp32 [B, N, ceil(T / C), K, V]; entry c holds
+ * the state BEFORE step c*C (entry 0 is H0).  Checkpoints replace the paper's
+ * H_full[B,T,N,K,V] cache (Algorithm 2, pass 1): the backward recomputes each
+ * chunk's states on chip from its checkpoint.  Returns 0 for an invalid
+ * descriptor or T == 0. */
+size_t m2rnn_ckpt_bytes(const m2rnn_desc *desc);
+
+/* Bytes of scratch the forward (bwd = 0) or backward (bwd != 0) call needs for
+ * partial sums across workgroups.  The backward figure includes room for
+ * checkpoints, used only when bwd is called with ckpt == NULL.  May be 0. */
+size_t m2rnn_workspace_bytes(const m2rnn_desc *desc, int bwd);
+
+/*
+ * Forward scan (Algorithm 1; recurrence equations).
+ *   q, k   [B,T,Nqk,K] io      v [B,T,N,V] io      f [B,T,N] fp32, gate VALUES in
+ *   [0,1] (the forget-gate function psi is applied by the caller)
+ *   W      [N,V,V] io          H0 [B,N,K,V] fp32 or NULL (zero initial state)
+ *   y      [B,T,N,V] io, out
+ *   HT     [B,N,K,V] fp32, out, final state; NULL if not wanted
+ *   ckpt   out, m2rnn_ckpt_bytes() bytes, written for a later m2rnn_bwd with the
+ *          same descriptor; NULL for inference (no checkpoints are written)
+ *   workspace / workspace_bytes  scratch of at least m2rnn_workspace_bytes(desc,0)
+ * Returns M2RNN_OK or the first validation / launch error.
+ */
+m2rnn_status m2rnn_fwd(const m2rnn_desc *desc, const void *q, const void *k,
+                       const void *v, const float *f, const void *W,
+                       const float *H0, void *y, float *HT, float *ckpt,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward scan (Algorithm 2, BPTT): gradients of
+ *     L = sum_{b,t,n,j} y * dy  +  sum_{b,n,i,j} HT * dHT
+ * with respect to q, k, v, f, W and H0.
+ *   q,k,v,f,W,H0  as in m2rnn_fwd (the same values)
+ *   ckpt   checkpoints written by m2rnn_fwd for this descriptor, or NULL: then
+ *          the library first re-runs the recurrence from H0 into the workspace
+ *          (the paper's pass 1, storing one state per chunk instead of all)
+ *   dy     [B,T,N,V] io        dHT [B,N,K,V] fp32 or NULL (zero)
+ *   dq, dk [B,T,Nqk,K] io, out (summed over the heads sharing a q/k head)
+ *   dv     [B,T,N,V] io, out   df [B,T,N] fp32, out (gradient w.r.t. the gate value)
+ *   dW     [N,V,V] fp32, out (summed over the batch)
+ *   dH0    [B,N,K,V] fp32, out; NULL if not wanted
+ *   workspace / workspace_bytes  at least m2rnn_workspace_bytes(desc,1)
+ */
+m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k,
+                       const void *v, const float *f, const void *W,
+                       const float *H0, const float *ckpt, const void *dy,
+                       const float *dHT, void *dq, void *dk, void *dv, float *df,
+                       float *dW, float *dH0, void *workspace,
+                       size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* M2RNN_H_ */

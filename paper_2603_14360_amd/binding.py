@@ -1,0 +1,167 @@
+"""Thin ctypes binding of libm2rnn.so (the C ABI in include/m2rnn.h).
+
+Same entry-point names as the header; this layer only marshals arguments:
+torch tensors own the device memory and supply the stream, every step of the
+scan runs inside the library's HIP kernels.  If the library is missing the
+import of any entry point raises -- there is no fallback.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libm2rnn.so")
+
+M2RNN_F32 = 0
+M2RNN_BF16 = 1
+
+EXPORTS = ("m2rnn_status_string", "m2rnn_default_chunk", "m2rnn_max_chunk",
+           "m2rnn_ckpt_bytes", "m2rnn_workspace_bytes", "m2rnn_fwd", "m2rnn_bwd")
+
+
+class m2rnn_desc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("N", ctypes.c_int32),
+                ("Nqk", ctypes.c_int32), ("K", ctypes.c_int32), ("V", ctypes.c_int32),
+                ("io", ctypes.c_int32), ("chunk", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+class M2RNNError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = int(code)
+        super().__init__("%s failed: [%d] %s" % (where, self.code, m2rnn_status_string(self.code)))
+
+
+_lib = None
+
+
+def lib():
+    """Loads libm2rnn.so once; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libm2rnn.so is not built (%s); run `python -m paper_2603_14360_amd.build`. "
+                "There is no fallback path." % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, dp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(m2rnn_desc)
+        L.m2rnn_status_string.restype = ctypes.c_char_p
+        L.m2rnn_status_string.argtypes = [ctypes.c_int]
+        L.m2rnn_default_chunk.restype = ctypes.c_int32
+        L.m2rnn_default_chunk.argtypes = [dp]
+        L.m2rnn_max_chunk.restype = ctypes.c_int32
+        L.m2rnn_max_chunk.argtypes = [dp]
+        L.m2rnn_ckpt_bytes.restype = sz
+        L.m2rnn_ckpt_bytes.argtypes = [dp]
+        L.m2rnn_workspace_bytes.restype = sz
+        L.m2rnn_workspace_bytes.argtypes = [dp, ctypes.c_int]
+        L.m2rnn_fwd.restype = ctypes.c_int
+        L.m2rnn_fwd.argtypes = [dp] + [vp] * 10 + [sz, vp]
+        L.m2rnn_bwd.restype = ctypes.c_int
+        L.m2rnn_bwd.argtypes = [dp] + [vp] * 16 + [sz, vp]
+        _lib = L
+    return _lib
+
+
+def make_desc(B, T, N, K, V, io, Nqk=None, chunk=0, flags=0):
+    return m2rnn_desc(B, T, N, N if Nqk is None else Nqk, K, V, io, chunk, flags)
+
+
+def m2rnn_status_string(code):
+    return lib().m2rnn_status_string(int(code)).decode()
+
+
+def m2rnn_default_chunk(desc):
+    return int(lib().m2rnn_default_chunk(ctypes.byref(desc)))
+
+
+def m2rnn_max_chunk(desc):
+    return int(lib().m2rnn_max_chunk(ctypes.byref(desc)))
+
+
+def m2rnn_ckpt_bytes(desc):
+    return int(lib().m2rnn_ckpt_bytes(ctypes.byref(desc)))
+
+
+def m2rnn_workspace_bytes(desc, bwd):
+    return int(lib().m2rnn_workspace_bytes(ctypes.byref(desc), int(bwd)))
+
+
+def _ptr(x):
+    """Device (or raw integer) address of a tensor; None -> NULL."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return ctypes.c_void_p(x)
+    return ctypes.c_void_p(x.data_ptr())
+
+
+def _nbytes(x):
+    return 0 if x is None else x.numel() * x.element_size()
+
+
+def m2rnn_fwd(desc, q, k, v, f, W, H0, y, HT, ckpt, workspace, stream=None, check=True):
+    """Raw call: every argument is a torch tensor on the GPU (or None where the
+    header allows NULL); `stream` is a raw hipStream_t handle (int) or None."""
+    rc = lib().m2rnn_fwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(f), _ptr(W),
+                         _ptr(H0), _ptr(y), _ptr(HT), _ptr(ckpt), _ptr(workspace),
+                         _nbytes(workspace), ctypes.c_void_p(stream or 0))
+    if check and rc != 0:
+        raise M2RNNError(rc, "m2rnn_fwd")
+    return rc
+
+
+def m2rnn_bwd(desc, q, k, v, f, W, H0, ckpt, dy, dHT, dq, dk, dv, df, dW, dH0, workspace,
+              stream=None, check=True):
+    rc = lib().m2rnn_bwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(f), _ptr(W),
+                         _ptr(H0), _ptr(ckpt), _ptr(dy), _ptr(dHT), _ptr(dq), _ptr(dk), _ptr(dv),
+                         _ptr(df), _ptr(dW), _ptr(dH0), _ptr(workspace), _nbytes(workspace),
+                         ctypes.c_void_p(stream or 0))
+    if check and rc != 0:
+        raise M2RNNError(rc, "m2rnn_bwd")
+    return rc
+
+
+# --------------------------------------------------------------------------
+# Buffer plumbing for callers that hold torch tensors: allocates outputs,
+# checkpoints and workspace with torch and calls the raw entry points on
+# torch's current stream.  No arithmetic happens here.
+class Scan:
+    """Owns the outputs / checkpoint / workspace buffers of one problem shape."""
+
+    def __init__(self, B, T, N, K, V, io, Nqk=None, chunk=0, backward=True, device="cuda"):
+        import torch
+        self.torch = torch
+        self.desc = make_desc(B, T, N, K, V, M2RNN_BF16 if io in ("bf16", M2RNN_BF16) else M2RNN_F32,
+                              Nqk=Nqk, chunk=chunk)
+        d = self.desc
+        self.io_dtype = torch.bfloat16 if d.io == M2RNN_BF16 else torch.float32
+        dev = device
+        self.y = torch.empty((B, T, N, V), dtype=self.io_dtype, device=dev)
+        self.HT = torch.empty((B, N, K, V), dtype=torch.float32, device=dev)
+        self.backward = backward
+        ws = m2rnn_workspace_bytes(d, 0)
+        if backward:
+            ws = max(ws, m2rnn_workspace_bytes(d, 1))
+            self.ckpt = torch.empty(max(1, m2rnn_ckpt_bytes(d) // 4), dtype=torch.float32, device=dev)
+            self.dq = torch.empty((B, T, d.Nqk, K), dtype=self.io_dtype, device=dev)
+            self.dk = torch.empty((B, T, d.Nqk, K), dtype=self.io_dtype, device=dev)
+            self.dv = torch.empty((B, T, N, V), dtype=self.io_dtype, device=dev)
+            self.df = torch.empty((B, T, N), dtype=torch.float32, device=dev)
+            self.dW = torch.empty((N, V, V), dtype=torch.float32, device=dev)
+            self.dH0 = torch.empty((B, N, K, V), dtype=torch.float32, device=dev)
+        else:
+            self.ckpt = None
+        self.workspace = torch.empty(max(ws, 256), dtype=torch.uint8, device=dev)
+
+    def _stream(self):
+        return self.torch.cuda.current_stream().cuda_stream
+
+    def fwd(self, q, k, v, f, W, H0=None):
+        m2rnn_fwd(self.desc, q, k, v, f, W, H0, self.y, self.HT, self.ckpt, self.workspace,
+                  stream=self._stream())
+        return self.y, self.HT
+
+    def bwd(self, q, k, v, f, W, H0, dy, dHT=None, use_ckpt=True):
+        m2rnn_bwd(self.desc, q, k, v, f, W, H0, self.ckpt if use_ckpt else None, dy, dHT,
+                  self.dq, self.dk, self.dv, self.df, self.dW, self.dH0, self.workspace,
+                  stream=self._stream())
+        return self.dq, self.dk, self.dv, self.df, self.dW, self.dH0

@@ -1,0 +1,182 @@
+// Host side of the C ABI declared in include/m2rnn.h: descriptor validation,
+// workspace sizing and the choice of kernel family.  No arithmetic of the
+// method happens here.
+#include "../../include/m2rnn.h"
+
+#include "m2rnn_kernels.hpp"
+
+using namespace m2rnn;
+
+namespace {
+
+bool dim_ok(int d) { return d == 16 || d == 32 || d == 64 || d == 128; }
+
+m2rnn_status check_desc(const m2rnn_desc *d) {
+  if (!d) return M2RNN_ERR_NULL;
+  if (d->io != M2RNN_F32 && d->io != M2RNN_BF16) return M2RNN_ERR_DTYPE;
+  if (d->B < 0 || d->T < 0 || d->N < 1 || d->Nqk < 1) return M2RNN_ERR_SHAPE;
+  if (d->N % d->Nqk != 0) return M2RNN_ERR_SHAPE;
+  if (!dim_ok(d->K) || !dim_ok(d->V)) return M2RNN_ERR_SHAPE;
+  if (d->flags != 0) return M2RNN_ERR_SHAPE;
+  // index arithmetic inside the kernels is 64-bit, but per-tensor element
+  // counts must stay below 2^40 to keep byte offsets far from overflow
+  const double big = (double)d->B * (double)(d->T > 0 ? d->T : 1) * d->N * d->K * d->V;
+  if (big > 1e15) return M2RNN_ERR_SHAPE;
+  return M2RNN_OK;
+}
+
+// Which kernel family serves this descriptor.
+enum Family { kGeneric = 0, kMfma = 1 };
+
+Family family_of(const m2rnn_desc *d) {
+  if (d->io == M2RNN_BF16 && mfma_supported(d->K, d->V)) return kMfma;
+  return kGeneric;
+}
+
+int default_chunk(const m2rnn_desc *d) {
+  return family_of(d) == kMfma ? mfma_default_chunk(d->K, d->V)
+                               : generic_default_chunk(d->K, d->V);
+}
+int max_chunk(const m2rnn_desc *d) {
+  return family_of(d) == kMfma ? mfma_max_chunk(d->K, d->V) : generic_max_chunk(d->K, d->V);
+}
+
+// Resolves desc.chunk; returns 0 if it is out of range.
+int resolve_chunk(const m2rnn_desc *d) {
+  if (d->chunk == 0) return default_chunk(d);
+  if (d->chunk < 0 || d->chunk > max_chunk(d)) return 0;
+  return d->chunk;
+}
+
+size_t ckpt_bytes(const m2rnn_desc *d, int C) {
+  if (d->T == 0) return 0;
+  return (size_t)d->B * d->N * ceil_div(d->T, C) * d->K * d->V * sizeof(float);
+}
+
+size_t family_ws(const m2rnn_desc *d, int C, int bwd) {
+  return family_of(d) == kMfma
+             ? mfma_workspace_bytes(d->B, d->T, d->N, d->Nqk, d->K, d->V, C, bwd)
+             : generic_workspace_bytes(d->B, d->T, d->N, d->Nqk, d->K, d->V, C, bwd);
+}
+
+bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char *m2rnn_status_string(m2rnn_status s) {
+  switch (s) {
+    case M2RNN_OK: return "ok";
+    case M2RNN_ERR_NULL: return "required pointer is NULL";
+    case M2RNN_ERR_SHAPE: return "unsupported shape (K, V in {16,32,64,128}; Nqk must divide N)";
+    case M2RNN_ERR_DTYPE: return "unknown io dtype";
+    case M2RNN_ERR_ALIGN: return "pointer is not 16-byte aligned";
+    case M2RNN_ERR_WORKSPACE: return "workspace too small";
+    case M2RNN_ERR_HIP: return "HIP call failed";
+    case M2RNN_ERR_CHUNK: return "checkpoint interval out of range";
+  }
+  return "unknown status";
+}
+
+int32_t m2rnn_default_chunk(const m2rnn_desc *desc) {
+  return check_desc(desc) == M2RNN_OK ? default_chunk(desc) : 0;
+}
+
+int32_t m2rnn_max_chunk(const m2rnn_desc *desc) {
+  return check_desc(desc) == M2RNN_OK ? max_chunk(desc) : 0;
+}
+
+size_t m2rnn_ckpt_bytes(const m2rnn_desc *desc) {
+  if (check_desc(desc) != M2RNN_OK) return 0;
+  const int C = resolve_chunk(desc);
+  return C ? ckpt_bytes(desc, C) : 0;
+}
+
+size_t m2rnn_workspace_bytes(const m2rnn_desc *desc, int bwd) {
+  if (check_desc(desc) != M2RNN_OK) return 0;
+  const int C = resolve_chunk(desc);
+  if (!C) return 0;
+  size_t need = family_ws(desc, C, bwd ? 1 : 0);
+  if (bwd) {
+    // room for the backward's own checkpoint pass (used when ckpt == NULL)
+    const size_t fwd_need = family_ws(desc, C, 0);
+    need = align256(need > fwd_need ? need : fwd_need) + align256(ckpt_bytes(desc, C));
+  }
+  return need;
+}
+
+m2rnn_status m2rnn_fwd(const m2rnn_desc *desc, const void *q, const void *k, const void *v,
+                       const float *f, const void *W, const float *H0, void *y, float *HT,
+                       float *ckpt, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  m2rnn_status st = check_desc(desc);
+  if (st != M2RNN_OK) return st;
+  const int C = resolve_chunk(desc);
+  if (!C) return M2RNN_ERR_CHUNK;
+  const bool empty = desc->B == 0;
+  const bool steps = !empty && desc->T > 0;
+  if (!W) return M2RNN_ERR_NULL;
+  if (steps && (!q || !k || !v || !f || !y)) return M2RNN_ERR_NULL;
+  const void *ptrs[] = {q, k, v, f, W, H0, y, HT, ckpt, workspace};
+  for (const void *p : ptrs)
+    if (misaligned(p)) return M2RNN_ERR_ALIGN;
+  const size_t need = family_ws(desc, C, 0);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return workspace ? M2RNN_ERR_WORKSPACE : M2RNN_ERR_NULL;
+
+  FwdArgs a;
+  a.B = desc->B; a.T = desc->T; a.N = desc->N; a.Nqk = desc->Nqk; a.K = desc->K; a.V = desc->V;
+  a.C = C; a.io = desc->io;
+  a.q = q; a.k = k; a.v = v; a.W = W; a.f = f; a.H0 = H0;
+  a.y = y; a.HT = HT; a.ckpt = ckpt; a.write_y = 1; a.ws = (char *)workspace;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const hipError_t e = family_of(desc) == kMfma ? mfma_fwd(a, s) : generic_fwd(a, s);
+  return e == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
+}
+
+m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k, const void *v,
+                       const float *f, const void *W, const float *H0, const float *ckpt,
+                       const void *dy, const float *dHT, void *dq, void *dk, void *dv, float *df,
+                       float *dW, float *dH0, void *workspace, size_t workspace_bytes,
+                       void *hip_stream) {
+  m2rnn_status st = check_desc(desc);
+  if (st != M2RNN_OK) return st;
+  const int C = resolve_chunk(desc);
+  if (!C) return M2RNN_ERR_CHUNK;
+  const bool steps = desc->B > 0 && desc->T > 0;
+  if (!W || !dW) return M2RNN_ERR_NULL;
+  if (steps && (!q || !k || !v || !f || !dy || !dq || !dk || !dv || !df)) return M2RNN_ERR_NULL;
+  const void *ptrs[] = {q, k, v, f, W, H0, ckpt, dy, dHT, dq, dk, dv, df, dW, dH0, workspace};
+  for (const void *p : ptrs)
+    if (misaligned(p)) return M2RNN_ERR_ALIGN;
+  const size_t need = m2rnn_workspace_bytes(desc, 1);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return workspace ? M2RNN_ERR_WORKSPACE : M2RNN_ERR_NULL;
+
+  hipStream_t s = (hipStream_t)hip_stream;
+  const Family fam = family_of(desc);
+  char *ws = (char *)workspace;
+  const size_t main_bytes = need - align256(ckpt_bytes(desc, C));
+  if (!ckpt && steps) {
+    // The paper's pass 1, keeping one state per chunk: rerun the recurrence
+    // from H0 without the readout, into the tail of the workspace.
+    float *own = (float *)(ws + main_bytes);
+    FwdArgs fa;
+    fa.B = desc->B; fa.T = desc->T; fa.N = desc->N; fa.Nqk = desc->Nqk; fa.K = desc->K;
+    fa.V = desc->V; fa.C = C; fa.io = desc->io;
+    fa.q = q; fa.k = k; fa.v = v; fa.W = W; fa.f = f; fa.H0 = H0;
+    fa.y = nullptr; fa.HT = nullptr; fa.ckpt = own; fa.write_y = 0; fa.ws = ws;
+    const hipError_t e = fam == kMfma ? mfma_fwd(fa, s) : generic_fwd(fa, s);
+    if (e != hipSuccess) return M2RNN_ERR_HIP;
+    ckpt = own;
+  }
+  BwdArgs a;
+  a.B = desc->B; a.T = desc->T; a.N = desc->N; a.Nqk = desc->Nqk; a.K = desc->K; a.V = desc->V;
+  a.C = C; a.io = desc->io;
+  a.q = q; a.k = k; a.v = v; a.W = W; a.dy = dy; a.f = f; a.H0 = H0; a.ckpt = ckpt; a.dHT = dHT;
+  a.dq = dq; a.dk = dk; a.dv = dv; a.df = df; a.dW = dW; a.dH0 = dH0; a.ws = ws;
+  const hipError_t e = fam == kMfma ? mfma_bwd(a, s) : generic_bwd(a, s);
+  return e == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
+}
+
+}  // extern "C"

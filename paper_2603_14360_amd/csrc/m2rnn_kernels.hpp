@@ -1,0 +1,49 @@
+// Internal declarations shared by the HIP translation units of libm2rnn.
+// Not part of the public ABI (that is include/m2rnn.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace m2rnn {
+
+// Arguments of one forward scan.  Shapes and meaning follow the public header;
+// pointers are device pointers.
+struct FwdArgs {
+  int B, T, N, Nqk, K, V, C, io;
+  const void *q, *k, *v, *W;
+  const float *f, *H0;
+  void *y;
+  float *HT, *ckpt;  // ckpt may be null (inference)
+  int write_y;       // 0: checkpoint-only pass (the backward's pass 1)
+  char *ws;          // workspace base (may be null when nothing is needed)
+};
+
+struct BwdArgs {
+  int B, T, N, Nqk, K, V, C, io;
+  const void *q, *k, *v, *W, *dy;
+  const float *f, *H0, *ckpt, *dHT;
+  void *dq, *dk, *dv;
+  float *df, *dW, *dH0;
+  char *ws;
+};
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ---- fp32 path (plain vector-ALU kernels; any supported shape, either io) ----
+int generic_default_chunk(int K, int V);
+int generic_max_chunk(int K, int V);
+size_t generic_workspace_bytes(int B, int T, int N, int Nqk, int K, int V, int C, int bwd);
+hipError_t generic_fwd(const FwdArgs &a, hipStream_t s);
+hipError_t generic_bwd(const BwdArgs &a, hipStream_t s);
+
+// ---- matrix-core path (bf16 io, fp16 MFMA operands, fp32 state) ----
+bool mfma_supported(int K, int V);
+int mfma_default_chunk(int K, int V);
+int mfma_max_chunk(int K, int V);
+size_t mfma_workspace_bytes(int B, int T, int N, int Nqk, int K, int V, int C, int bwd);
+hipError_t mfma_fwd(const FwdArgs &a, hipStream_t s);
+hipError_t mfma_bwd(const BwdArgs &a, hipStream_t s);
+
+}  // namespace m2rnn

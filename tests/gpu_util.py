@@ -1,0 +1,74 @@
+"""Helpers for the GPU parity tests: move a seeded input set to the device,
+run the library through its C ABI, run the float64 oracle on the same values,
+and compare tensor by tensor with  max|gpu - oracle| / max|oracle|."""
+import numpy as np
+
+import oracle
+from paper_2603_14360_amd import binding as mb
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+GRAD_NAMES = ("dq", "dk", "dv", "df", "dW", "dH0")
+
+
+def to_device(inp, io):
+    import torch
+    dt = torch.bfloat16 if io == "bf16" else torch.float32
+    dev = {}
+    for name in ("q", "k", "v", "W", "dy"):
+        dev[name] = torch.from_numpy(np.ascontiguousarray(inp[name], dtype=np.float32)).to("cuda").to(dt)
+    dev["f"] = torch.from_numpy(np.ascontiguousarray(inp["f"], dtype=np.float32)).to("cuda")
+    for name in ("H0", "dHT"):
+        x = inp.get(name)
+        dev[name] = None if x is None else torch.from_numpy(
+            np.ascontiguousarray(x, dtype=np.float32)).to("cuda")
+    return dev
+
+
+def to_np(x):
+    return x.detach().to("cpu").float().numpy().astype(np.float64)
+
+
+def run_gpu(inp, io, chunk=0, backward=True, use_ckpt=True):
+    """Returns dict of float64 numpy outputs from the HIP library."""
+    import torch
+    B, T, Nqk, K = inp["q"].shape
+    N, V = inp["v"].shape[2], inp["v"].shape[3]
+    dev = to_device(inp, io)
+    scan = mb.Scan(B, T, N, K, V, io, Nqk=Nqk, chunk=chunk, backward=backward)
+    y, HT = scan.fwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"])
+    out = {"y": to_np(y), "HT": to_np(HT)}
+    if backward:
+        g = scan.bwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"], dev["dy"],
+                     dev["dHT"], use_ckpt=use_ckpt)
+        for name, x in zip(GRAD_NAMES, g):
+            out[name] = to_np(x)
+    torch.cuda.synchronize()
+    return out
+
+
+def run_oracle(inp, backward=True):
+    args = [inp[n] for n in ("q", "k", "v", "f", "W")]
+    y, HT = oracle.fwd(*args, inp.get("H0"))
+    out = {"y": y, "HT": HT}
+    if backward:
+        g = oracle.bwd(*args, inp.get("H0"), inp["dy"], inp.get("dHT"))
+        out.update(dict(zip(GRAD_NAMES, g)))
+    return out
+
+
+def rel_err(got, ref):
+    den = np.abs(ref).max() if ref.size else 0.0
+    num = np.abs(got - ref).max() if ref.size else 0.0
+    return num / den if den > 0 else num
+
+
+def compare(got, ref, tol, names=None, label=""):
+    """Asserts every tensor is within tol; returns {name: err}."""
+    errs = {}
+    for name in (names or ref.keys()):
+        assert got[name].shape == ref[name].shape, (label, name, got[name].shape, ref[name].shape)
+        assert np.isfinite(got[name]).all(), (label, name, "non-finite values")
+        errs[name] = rel_err(got[name], ref[name])
+    bad = {n: e for n, e in errs.items() if not e <= tol}
+    assert not bad, "%s: over tolerance %g: %s (all: %s)" % (label, tol, bad, errs)
+    return errs

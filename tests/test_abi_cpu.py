@@ -1,0 +1,115 @@
+"""CPU-only: the C-ABI library loads, exports every symbol the header declares,
+sizes its buffers sensibly and rejects bad calls on the host before anything is
+launched (no GPU is touched by these tests)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_14360_amd import binding as mb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "m2rnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(m2rnn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = declared_functions()
+    assert set(names) == set(mb.EXPORTS)
+    L = mb.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings():
+    seen = {mb.m2rnn_status_string(c) for c in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+
+
+def desc(**kw):
+    base = dict(B=2, T=32, N=4, K=32, V=32, io=mb.M2RNN_F32)
+    base.update(kw)
+    return mb.make_desc(**base)
+
+
+def test_sizes():
+    d = desc()
+    C = mb.m2rnn_default_chunk(d)
+    assert 1 <= C <= mb.m2rnn_max_chunk(d)
+    assert mb.m2rnn_ckpt_bytes(d) == 2 * 4 * ((32 + C - 1) // C) * 32 * 32 * 4
+    assert mb.m2rnn_workspace_bytes(d, 1) >= mb.m2rnn_workspace_bytes(d, 0)
+    assert mb.m2rnn_workspace_bytes(d, 1) >= mb.m2rnn_ckpt_bytes(d)
+    assert mb.m2rnn_ckpt_bytes(desc(T=0)) == 0
+    d7 = desc(chunk=7)
+    assert mb.m2rnn_ckpt_bytes(d7) == 2 * 4 * 5 * 32 * 32 * 4
+    for io in (mb.M2RNN_F32, mb.M2RNN_BF16):
+        for K in (16, 32, 64, 128):
+            for V in (16, 32, 64, 128):
+                dd = desc(K=K, V=V, io=io)
+                assert mb.m2rnn_default_chunk(dd) >= 1
+                assert mb.m2rnn_workspace_bytes(dd, 1) > 0
+
+
+class FakeBuf:
+    """Stands in for a device buffer in host-side validation tests."""
+
+    def __init__(self, addr, nbytes):
+        self.addr, self.nbytes = addr, nbytes
+
+    def data_ptr(self):
+        return self.addr
+
+    def numel(self):
+        return self.nbytes
+
+    def element_size(self):
+        return 1
+
+
+BAD = [
+    (dict(K=24), 2), (dict(V=256), 2), (dict(K=0), 2), (dict(N=0), 2), (dict(Nqk=3), 2),
+    (dict(B=-1), 2), (dict(T=-5), 2), (dict(io=7), 3), (dict(flags=1), 2),
+    (dict(chunk=-1), 7), (dict(chunk=1 << 20), 7),
+]
+
+
+@pytest.mark.parametrize("kw,code", BAD)
+def test_bad_descriptor_rejected(kw, code):
+    d = desc(**kw)
+    A = 0x1000  # a well-aligned non-null address that is never dereferenced
+    ws = FakeBuf(0x100000, 1 << 40)
+    rc = mb.m2rnn_fwd(d, A, A, A, A, A, None, A, None, None, ws, check=False)
+    assert rc == code
+    rc = mb.m2rnn_bwd(d, A, A, A, A, A, None, None, A, None, A, A, A, A, A, None, ws, check=False)
+    assert rc == code
+    if code != 7:
+        assert mb.m2rnn_workspace_bytes(d, 1) == 0 and mb.m2rnn_ckpt_bytes(d) == 0
+    assert mb.m2rnn_default_chunk(d) == 0 or code == 7
+
+
+def test_null_alignment_workspace_errors():
+    d = desc()
+    A = 0x1000
+    big = FakeBuf(0x100000, 1 << 40)
+    # required pointer missing
+    assert mb.m2rnn_fwd(d, None, A, A, A, A, None, A, None, None, big, check=False) == 1
+    assert mb.m2rnn_fwd(d, A, A, A, A, None, None, A, None, None, big, check=False) == 1
+    assert mb.m2rnn_bwd(d, A, A, A, A, A, None, None, A, None, A, A, A, A, None, None, big,
+                        check=False) == 1
+    # misaligned pointer
+    assert mb.m2rnn_fwd(d, A + 4, A, A, A, A, None, A, None, None, big, check=False) == 4
+    assert mb.m2rnn_bwd(d, A, A, A, A, A, None, None, A + 8, None, A, A, A, A, A, None, big,
+                        check=False) == 4
+    # workspace too small / missing
+    small = FakeBuf(0x100000, 16)
+    assert mb.m2rnn_fwd(d, A, A, A, A, A, None, A, None, None, small, check=False) == 5
+    assert mb.m2rnn_bwd(d, A, A, A, A, A, None, None, A, None, A, A, A, A, A, None, small,
+                        check=False) == 5
+    assert mb.m2rnn_fwd(d, A, A, A, A, A, None, A, None, None, None, check=False) == 1
+    with pytest.raises(mb.M2RNNError):
+        mb.m2rnn_fwd(d, None, A, A, A, A, None, A, None, None, big)
