@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the M2RNN scan hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3]
+
+One "step" is one pass of the whole hot path over one batch of synthetic
+input: m2rnn_fwd (writing checkpoints) followed by m2rnn_bwd, both through the
+C ABI, inputs resident in HBM before the timed region.  Prints ONE JSON line:
+tokens/s (tokens = B*T per step), the roofline object of the dominant kernel
+(the backward scan) and the float64 oracle timed on the host cores.
+
+The roofline is the vector-ALU one (tanh and gating bind this path, not the
+matrix cores or HBM): algorithmic lane-operations per element-step, with a
+transcendental counted as two issue slots (measured half rate on gfx950),
+against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-op/s.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# Algorithmic vector-ALU work per state element per time step:
+# (plain fp32 ops, transcendental ops)
+ALU_OPS = {"fwd": (7, 2), "bwd": (14, 2)}
+TRANS_SLOTS = 2                       # issue slots of v_exp_f32 / v_rcp_f32 relative to v_fma_f32
+PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9  # lane-ops per second, packed fp32 not used
+
+
+def alu_slots(kind):
+    v, t = ALU_OPS[kind]
+    return v + TRANS_SLOTS * t
+
+
+def cpu_baseline(wl, inp):
+    """The float64 oracle, as it stands, on a bounded sample of the workload:
+    whole (batch, head) recurrences at full T for as many heads as it takes to
+    give every host thread one recurrence."""
+    import oracle
+    from paper_2603_14360_amd.synth_inputs import select_heads
+    threads = oracle.num_threads()
+    heads = max(1, min(wl.N, -(-threads // wl.B)))
+    # keep the sample to roughly 10-30 s: shorten T for the big-state workloads
+    T = wl.T
+    cost = wl.B * heads * T * wl.K * wl.V * wl.V / max(1, threads)
+    while cost > 6e9 and T > 256:
+        T //= 2
+        cost /= 2
+    sub = select_heads(inp, list(range(heads)))
+    for n in ("q", "k", "v", "f", "dy"):
+        sub[n] = sub[n][:, :T]
+    args = [sub[n] for n in ("q", "k", "v", "f", "W")]
+    t0 = time.perf_counter()
+    oracle.fwd(*args, sub["H0"])
+    if wl.backward:
+        oracle.bwd(*args, sub["H0"], sub["dy"], sub["dHT"])
+    dt = time.perf_counter() - t0
+    tokens_equiv = wl.B * T * heads / wl.N   # tokens span all N heads
+    return {"value": tokens_equiv / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of %d heads x all %d batch rows, T=%d of %d, fwd%s, %.1f s wall; "
+                      "tokens scaled by heads/N" % (heads, wl.N, wl.B, T, wl.T,
+                                                    "+bwd" if wl.backward else "", dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the scan has no multi-GPU path); "
+                 "--gpus %d is not supported" % args.gpus)
+
+    import numpy as np
+    import torch
+    from paper_2603_14360_amd import binding as mb
+    from paper_2603_14360_amd.synth_inputs import WORKLOADS, make_inputs
+
+    mb.lib()  # fail loudly when the HIP library is missing
+    wl = WORKLOADS[args.workload]
+    inp = make_inputs(wl)
+    io_dt = torch.bfloat16 if wl.io == "bf16" else torch.float32
+    dev = {}
+    for n in ("q", "k", "v", "W", "dy"):
+        dev[n] = torch.from_numpy(inp[n]).to("cuda").to(io_dt)
+    dev["f"] = torch.from_numpy(inp["f"]).to("cuda")
+    for n in ("H0", "dHT"):
+        dev[n] = None if inp[n] is None else torch.from_numpy(inp[n]).to("cuda")
+    scan = mb.Scan(wl.B, wl.T, wl.N, wl.K, wl.V, wl.io, backward=wl.backward)
+
+    def step():
+        scan.fwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"])
+        if wl.backward:
+            scan.bwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"], dev["dy"],
+                     dev["dHT"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # HIP events on the stream the library launches on (torch's current stream)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        scan.fwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"])
+        ev[i][1].record()
+        if wl.backward:
+            scan.bwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"], dev["dy"],
+                     dev["dHT"])
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev])) if wl.backward else 0.0
+
+    ms_per_step = wall * 1e3 / args.steps
+    tokens = wl.B * wl.T
+    elem_steps = wl.B * wl.N * wl.T * wl.K * wl.V
+    dom = "bwd" if wl.backward else "fwd"
+    dom_ms = bwd_ms if wl.backward else fwd_ms
+    achieved = elem_steps * alu_slots(dom) / (dom_ms * 1e-3)
+    step_slots = alu_slots("fwd") + (alu_slots("bwd") if wl.backward else 0)
+    out = {
+        "metric": "M2RNN fwd+bwd tokens/s on 1 MI355X" if wl.backward else "M2RNN fwd tokens/s on 1 MI355X",
+        "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 state, f16 matrix-core operands, bf16 io" if wl.io == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: B=%d N=%d K=%d V=%d T=%d %s io, fwd%s" % (
+            wl.name, wl.B, wl.N, wl.K, wl.V, wl.T, wl.io, "+bwd" if wl.backward else ""),
+            "tokens_per_step": tokens, "chunk": mb.m2rnn_default_chunk(scan.desc)},
+        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "roofline": {
+            "bound": "alu", "kernel": "m2rnn_%s (scan kernel of the %s call)" % (dom, dom),
+            "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
+            "frac": achieved / PEAK_LANE_OPS, "traffic": None,
+            "step_frac": elem_steps * step_slots / (ms_per_step * 1e-3) / PEAK_LANE_OPS,
+            "fwd_frac": elem_steps * alu_slots("fwd") / (fwd_ms * 1e-3) / PEAK_LANE_OPS,
+            "mfma_tflops": elem_steps * wl.V * (2 + (6 if wl.backward else 0)) / (ms_per_step * 1e-3) / 1e12,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, inp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
