@@ -25,12 +25,33 @@ m2rnn_status check_desc(const m2rnn_desc *d) {
   return M2RNN_OK;
 }
 
-// Which kernel family serves this descriptor.
-enum Family { kGeneric = 0, kMfma = 1 };
+// Which kernel family serves this descriptor.  The checkpoint layout is common
+// to all families, so forward and backward may come from different ones.
+enum Family { kGeneric = 0, kMfma = 1, kRowWave = 2 };
 
-Family family_of(const m2rnn_desc *d) {
+Family family_of(const m2rnn_desc *d) {  // backward (it owns the chunk limits)
   if (d->io == M2RNN_BF16 && mfma_supported(d->K, d->V)) return kMfma;
   return kGeneric;
+}
+
+Family fwd_family_of(const m2rnn_desc *d) {
+  // The register-resident kernel needs no LDS exchange but one wave carries a
+  // whole 16-row block; it pays off once there are enough row blocks for at
+  // least two waves per SIMD (1024 SIMDs).  Below that the tiled kernel, which
+  // spreads a row block over V/16 waves, keeps more of the chip busy.
+  if (d->io == M2RNN_BF16 && rowwave_supported(d->K, d->V)) {
+    const long long row_blocks = (long long)d->B * d->N * (d->K / 16);
+    if (row_blocks >= 2048 || !mfma_supported(d->K, d->V)) return kRowWave;
+  }
+  return family_of(d);
+}
+
+hipError_t run_fwd(const m2rnn_desc *d, const FwdArgs &a, hipStream_t s) {
+  switch (fwd_family_of(d)) {
+    case kRowWave: return rowwave_fwd(a, s);
+    case kMfma: return mfma_fwd(a, s);
+    default: return generic_fwd(a, s);
+  }
 }
 
 int default_chunk(const m2rnn_desc *d) {
@@ -54,9 +75,10 @@ size_t ckpt_bytes(const m2rnn_desc *d, int C) {
 }
 
 size_t family_ws(const m2rnn_desc *d, int C, int bwd) {
-  return family_of(d) == kMfma
-             ? mfma_workspace_bytes(d->B, d->T, d->N, d->Nqk, d->K, d->V, C, bwd)
-             : generic_workspace_bytes(d->B, d->T, d->N, d->Nqk, d->K, d->V, C, bwd);
+  const Family fam = bwd ? family_of(d) : fwd_family_of(d);
+  if (fam == kRowWave) return 0;
+  return fam == kMfma ? mfma_workspace_bytes(d->B, d->T, d->N, d->Nqk, d->K, d->V, C, bwd)
+                      : generic_workspace_bytes(d->B, d->T, d->N, d->Nqk, d->K, d->V, C, bwd);
 }
 
 bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
@@ -130,7 +152,7 @@ m2rnn_status m2rnn_fwd(const m2rnn_desc *desc, const void *q, const void *k, con
   a.q = q; a.k = k; a.v = v; a.W = W; a.f = f; a.H0 = H0;
   a.y = y; a.HT = HT; a.ckpt = ckpt; a.write_y = 1; a.ws = (char *)workspace;
   hipStream_t s = (hipStream_t)hip_stream;
-  const hipError_t e = family_of(desc) == kMfma ? mfma_fwd(a, s) : generic_fwd(a, s);
+  const hipError_t e = run_fwd(desc, a, s);
   return e == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
 }
 
@@ -166,7 +188,7 @@ m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k, con
     fa.V = desc->V; fa.C = C; fa.io = desc->io;
     fa.q = q; fa.k = k; fa.v = v; fa.W = W; fa.f = f; fa.H0 = H0;
     fa.y = nullptr; fa.HT = nullptr; fa.ckpt = own; fa.write_y = 0; fa.ws = ws;
-    const hipError_t e = fam == kMfma ? mfma_fwd(fa, s) : generic_fwd(fa, s);
+    const hipError_t e = run_fwd(desc, fa, s);
     if (e != hipSuccess) return M2RNN_ERR_HIP;
     ckpt = own;
   }

@@ -30,13 +30,14 @@ constexpr int kChunkCap = 16;
 
 template <typename TL>
 struct BwdLds {
-  static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, RB = TL::RB, CT = TL::CT,
-                       WAVES = TL::WAVES;
-  static constexpr int X_BYTES = 2 * ROWS * LDH * 2;      // exchange (state in A, dS in B)
+  static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, LDH2 = TL::LDH2, RB = TL::RB,
+                       CT = TL::CT, WAVES = TL::WAVES;
+  static constexpr int X_BYTES = 2 * ROWS * LDH2 * 2;     // exchange: (hi, lo) state in phase A,
+                                                          // fp16 dS in phase B
   static constexpr int STASH_STEP = RB * CT * 64 * 8;     // one h4 per lane per tile
-  static constexpr int VEC_STEP = ROWS * (4 + 4 + 2) + V * (4 + 4 + 2 + 2) + 16;
+  static constexpr int VEC_STEP = ROWS * (4 + 4 + 2) + V * (4 + 4 + 2 + 4) + 16;
   static constexpr int PER_STEP = 2 * STASH_STEP + VEC_STEP;
-  static constexpr int PART_BYTES = 2 * RB * V * 4 + 2 * WAVES * 4 * 4;
+  static constexpr int PART_BYTES = 2 * RB * V * 4;
   static constexpr int FIXED = X_BYTES + PART_BYTES;
   static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 64) / PER_STEP;
   static constexpr int CMAX = CMAX_RAW > kChunkCap ? kChunkCap : CMAX_RAW;
@@ -51,11 +52,10 @@ struct BwdLds {
   static constexpr int DYS_ = VS_ + CMAX * V * 4;         // float dy    [C][V]
   static constexpr int KH_ = DYS_ + CMAX * V * 4;         // half k      [C][ROWS]
   static constexpr int VH_ = KH_ + CMAX * ROWS * 2;       // half v      [C][V]
-  static constexpr int DYH_ = VH_ + CMAX * V * 2;         // half dy     [C][V]
-  static constexpr int FS_ = DYH_ + CMAX * V * 2;         // float f, c(1-f), 1-f, -2c(1-f) [C][4]
+  static constexpr int DYH_ = VH_ + CMAX * V * 2;         // half dy, each value twice [C][2V]
+  static constexpr int FS_ = DYH_ + CMAX * V * 4;         // float f, c(1-f), 1-f, -2c(1-f) [C][4]
   static constexpr int DVP_ = FS_ + CMAX * 16;            // float [2][RB][V]
-  static constexpr int DFP_ = DVP_ + 2 * RB * V * 4;      // float [2][WAVES*4]
-  static constexpr int BYTES = DFP_ + 2 * WAVES * 4 * 4;
+  static constexpr int BYTES = DVP_ + 2 * RB * V * 4;
   static_assert(BYTES <= kLdsLimit, "LDS overflow");
 };
 
@@ -73,9 +73,20 @@ __device__ __forceinline__ float row16_sum(float x) {
   return x;
 }
 
+// sum over all 64 lanes; the total is valid in lane 63
+__device__ __forceinline__ float wave_sum_to_lane63(float x) {
+  x = row16_sum(x);
+  // row_bcast15 (rows 1,3 += last lane of rows 0,2), then row_bcast31 (rows 2,3 += lane 31)
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x142,
+                                                             0xa, 0xf, false));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x143,
+                                                             0xc, 0xf, false));
+  return x;
+}
+
 struct BwdWs {
   float *dvp;   // [P][B,T,N,V]      (P > 1)
-  float *dfp;   // [P][B,T,N]        (P > 1)
+  float *dfp;   // [P*WAVES][B,T,N]  per-wave partials of df, summed by the epilogue
   float *dWp;   // [B*N][P*RB][V][V]
   float *dqh;   // [B,T,N,K]         (Nqk != N)
   float *dkh;
@@ -84,7 +95,7 @@ struct BwdWs {
 template <typename TL>
 __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs ws) {
   constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS, KS = TL::KS,
-                LDH = TL::LDH, WAVES = TL::WAVES;
+                LDH = TL::LDH, LDH2 = TL::LDH2, WAVES = TL::WAVES, GROUPS = TL::GROUPS;
   constexpr int THREADS = TL::THREADS;
   constexpr bool X32 = TL::X32;
   constexpr int FE = X32 ? 8 : 4;
@@ -101,13 +112,18 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
   const int g = n / (N / a.Nqk);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rb = wave / CT, ct = wave - rb * CT;
+  const int grp = GROUPS == 2 ? rb / (RB / 2) : 0;
   const int jl = lane & 15, ig = lane >> 4;
   const int col0 = ct * 16, rowb = rb * 16;
   const int row_base = part * ROWS;
+  // the per-row-block extras (dq in phase A, dk in phase B) are dealt to different waves
+  const int dq_ct = rb % CT, dk_ct = (rb + 1) % CT;
 
   extern __shared__ __attribute__((aligned(16))) char lds[];
+  typedef _Float16 XRow2[LDH2];
   typedef _Float16 XRow[LDH];
-  XRow *Xb = (XRow *)(lds + L::X);                  // [2*ROWS][LDH]
+  XRow2 *Hx = (XRow2 *)(lds + L::X);                // phase A view: [2*ROWS][LDH2], (hi, lo) pairs
+  XRow *Dx = (XRow *)(lds + L::X);                  // phase B view: [2*ROWS][LDH], fp16 dS
   h4_t *stH = (h4_t *)(lds + L::SH);                // [C][RB][CT][64]
   h4_t *stZ = (h4_t *)(lds + L::SZ);
   float *kS = (float *)(lds + L::KS_);
@@ -119,8 +135,6 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
   _Float16 *dyH = (_Float16 *)(lds + L::DYH_);
   float *fS = (float *)(lds + L::FS_);
   float *dvP = (float *)(lds + L::DVP_);
-  float *dfP = (float *)(lds + L::DFP_);
-  auto X = [&](int buf, int row) -> _Float16 * { return Xb[buf * ROWS + row]; };
 
   const bf16_raw *__restrict__ qg = (const bf16_raw *)a.q;
   const bf16_raw *__restrict__ kg = (const bf16_raw *)a.k;
@@ -128,17 +142,28 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
   const bf16_raw *__restrict__ dyg = (const bf16_raw *)a.dy;
   const float *__restrict__ fg = a.f;
 
-  // ---- W fragments.  wf: B[k = c][n = j] = W[c][col0 + jl] (recompute);
-  //      wtf: B[k = j][n = c] = W[col0 + jl][j] (carry contraction, W^T)
-  FragT wf[KS], wtf[KS];
+  // ---- W fragments.
+  //  wf : recompute, B[k][n = j]: k-slots 2e, 2e+1 of MFMA m hold W[16 m + 4 ig + e][col0 + jl]
+  //       (they meet the (hi, lo) pair of that state element);
+  //  wtf: carry contraction with W^T, B[k = j][n = c] = W[col0 + jl][j]
+  h8_t wf[CT];
+  FragT wtf[KS];
   {
     const bf16_raw *Wn = (const bf16_raw *)a.W + (size_t)n * V * V;
+#pragma unroll
+    for (int m = 0; m < CT; ++m)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int c = 16 * m + 4 * ig + e;
+        const _Float16 w = (_Float16)bf16_to_f32(Wn[(size_t)c * V + col0 + jl]);
+        wf[m][2 * e] = w;
+        wf[m][2 * e + 1] = w;
+      }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
       for (int e = 0; e < FE; ++e) {
         const int kk = FE * ig + e + 32 * ks;
-        wf[ks][e] = (_Float16)bf16_to_f32(Wn[(size_t)kk * V + col0 + jl]);
         wtf[ks][e] = (_Float16)bf16_to_f32(Wn[(size_t)(col0 + jl) * V + kk]);
       }
   }
@@ -186,6 +211,12 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
     for (int r = 0; r < 4; ++r) hck[r] = src[(size_t)r * V];
   };
   auto stage_store = [&]() {
+    // keep the conversions here: hoisted to the loads they would wait for the loads at once
+#pragma unroll
+    for (int m = 0; m < NQ; ++m) asm volatile("" : "+v"(rq[m]), "+v"(rk[m]));
+#pragma unroll
+    for (int m = 0; m < NV; ++m) asm volatile("" : "+v"(rv[m]), "+v"(rdy[m]));
+    asm volatile("" : "+v"(rf), "+v"(hck[0]), "+v"(hck[1]), "+v"(hck[2]), "+v"(hck[3]));
 #pragma unroll
     for (int m = 0; m < NQ; ++m) {
       const int idx = tid + m * THREADS;
@@ -200,11 +231,12 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
     for (int m = 0; m < NV; ++m) {
       const int idx = tid + m * THREADS;
       if (idx < CMAX * V) {
-        const float vf = bf16_to_f32(rv[m]), df_ = bf16_to_f32(rdy[m]);
+        const float vf = bf16_to_f32(rv[m]), dyf = bf16_to_f32(rdy[m]);
         vS[idx] = vf;
         vH[idx] = (_Float16)vf;
-        dyS[idx] = df_;
-        dyH[idx] = (_Float16)df_;
+        dyS[idx] = dyf;
+        dyH[2 * idx] = (_Float16)dyf;
+        dyH[2 * idx + 1] = (_Float16)dyf;
       }
     }
     if (tid < CMAX) {
@@ -215,16 +247,14 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
     }
   };
 
-  // dq_t = H_t dy_t  from the A fragments of H'_t (done by the ct == 0 wave of a row block)
-  auto emit_dq = [&](const FragT *af, int s_prev, int t_prev) {
+  // dq_t = H_t dy_t from the A fragments of H'_t = (hi, lo) pairs; B repeats dy likewise.
+  // Done by the ct == 0 wave of each row block.
+  auto emit_dq = [&](const h8_t *af, int s_prev, int t_prev) {
     f4_t d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const FragT bf = *(const FragT *)&dyH[s_prev * V + FE * ig + 32 * ks];
-      if constexpr (X32)
-        d = mfma_k32(af[ks], bf, d);
-      else
-        d = mfma_k16(af[ks], bf, d);
+    for (int m = 0; m < CT; ++m) {
+      const h8_t bf = *(const h8_t *)&dyH[s_prev * 2 * V + 2 * (16 * m + 4 * ig)];
+      d = mfma_k32(af[m], bf, d);
     }
     if (jl == 0) {
       d *= kInvC;
@@ -240,9 +270,22 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
     }
   };
 
+  // sums over the row blocks / waves of this workgroup for one finished step
+  auto finish_dv_df = [&](int par, int t) {
+    if (rb == 0 && lane < 16) {
+      float sdv = dvP[(par * RB + 0) * V + col0 + jl];
+#pragma unroll
+      for (int r2 = 1; r2 < RB; ++r2) sdv += dvP[(par * RB + r2) * V + col0 + jl];
+      const size_t off = (((size_t)b * T + t) * N + n) * V + col0 + jl;
+      if constexpr (TL::P == 1)
+        ((bf16_raw *)a.dv)[off] = f32_to_bf16(sdv);
+      else
+        ws.dvp[(size_t)part * a.B * T * N * V + off] = sdv;
+    }
+  };
+
   if (nck > 0) stage_load(nck - 1);
 
-  int cur = 0;
   for (int ck = nck - 1; ck >= 0; --ck) {
     const int t0 = ck * C;
     const int len = (T - t0) < C ? (T - t0) : C;
@@ -250,33 +293,36 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
     // ================= phase A: recompute the chunk, fill the stash
     stage_store();
     float h[4];
-    h4_t hp;
+    uint32_t pk[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       h[r] = kC * hck[r];
-      hp[r] = (_Float16)h[r];
+      pk[r] = split_hi_lo(h[r]);
     }
+    int cur = 0;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) X(cur, rowb + 4 * ig + r)[col0 + jl] = hp[r];
-    __syncthreads();
+    for (int r = 0; r < 4; ++r)
+      *(uint32_t *)&Hx[cur * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+    lds_barrier();
+    if (GROUPS == 2 && grp == 1) lds_barrier();  // second group runs half a step behind
 
     for (int s = 0; s < len; ++s) {
+      // ---- R: contraction (and dq of the previous step)
+      h8_t af[CT];
+#pragma unroll
+      for (int m = 0; m < CT; ++m)
+        af[m] = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * m + 4 * ig)];
       const float f = fS[s * 4 + 0], gp = fS[s * 4 + 1], m2g = fS[s * 4 + 3];
       const f4_t k4 = *(const f4_t *)&kS[s * ROWS + rowb + 4 * ig];
       const float vj = vS[s * V + col0 + jl];
-      FragT af[KS];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) af[ks] = *(const FragT *)&X(cur, rowb + jl)[FE * ig + 32 * ks];
       f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        if constexpr (X32)
-          acc = mfma_k32(af[ks], wf[ks], acc);
-        else
-          acc = mfma_k16(af[ks], wf[ks], acc);
-      }
-      if (ct == 0 && s > 0) emit_dq(af, s - 1, t0 + s - 1);
-      stH[((s * RB + rb) * CT + ct) * 64 + lane] = hp;  // H'_{t-1}, this tile
+      for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
+      if (ct == dq_ct && s > 0) emit_dq(af, s - 1, t0 + s - 1);
+      if (GROUPS == 2) lds_barrier();
+
+      // ---- E: tanh, gate, stash, write back
+      stH[((s * RB + rb) * CT + ct) * 64 + lane] = hi_of_pairs(pk);  // hi(H'_{t-1}), this tile
       h4_t zp;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -288,28 +334,35 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
         const float z = fmaf(-2.f * kC, rr, kC);  // c tanh(s)
         h[r] = fmaf(m2g, rr, t1);
         zp[r] = (_Float16)z;
-        hp[r] = (_Float16)h[r];
+        pk[r] = split_hi_lo(h[r]);
       }
       stZ[((s * RB + rb) * CT + ct) * 64 + lane] = zp;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) X(cur ^ 1, rowb + 4 * ig + r)[col0 + jl] = hp[r];
-      __syncthreads();
+      for (int r = 0; r < 4; ++r)
+        *(uint32_t *)&Hx[(cur ^ 1) * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+      lds_barrier();
       cur ^= 1;
     }
-    if (ct == 0) {  // dq of the chunk's last step, from the state after it
-      FragT af[KS];
+    if (GROUPS == 2 && grp == 0) lds_barrier();  // let the second group finish its last step
+    if (ct == dq_ct) {  // dq of the chunk's last step, from the state after it
+      h8_t af[CT];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) af[ks] = *(const FragT *)&X(cur, rowb + jl)[FE * ig + 32 * ks];
+      for (int m = 0; m < CT; ++m)
+        af[m] = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * m + 4 * ig)];
       emit_dq(af, len - 1, t0 + len - 1);
     }
-    __syncthreads();  // X is reused for dS from here on
+    lds_barrier();  // the exchange buffer is reused for dS from here on
 
     // ================= phase B: reverse sweep over the chunk
-    // keep this chunk's tail of vectors in LDS; fetch the next chunk's into registers
+    // this chunk's vectors stay in LDS; the next chunk's are fetched into registers
     if (ck > 0) stage_load(ck - 1);
+    if (GROUPS == 2 && grp == 1) lds_barrier();
+    cur = 0;
 
     for (int s = len - 1; s >= 0; --s) {
       const int t = t0 + s;
+      const int par = s & 1;
+      // ---- E1: G, df, dS and the contractions over rows
       const float f = fS[s * 4 + 0], gm = fS[s * 4 + 2];
       const f4_t q4 = *(const f4_t *)&qS[s * ROWS + rowb + 4 * ig];
       const float dyj = dyS[s * V + col0 + jl];
@@ -317,7 +370,10 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
       h4_t hfr[CT];
 #pragma unroll
       for (int c2 = 0; c2 < CT; ++c2) hfr[c2] = stH[((s * RB + rb) * CT + c2) * 64 + lane];
+      // this wave's own tile again (indexing hfr[] with the runtime ct would turn into selects)
+      const h4_t hown = stH[((s * RB + rb) * CT + ct) * 64 + lane];
       const h4_t kfr = *(const h4_t *)&kH[s * ROWS + rowb + 4 * ig];
+      if (GROUPS == 2 && s < len - 1) finish_dv_df(par ^ 1, t + 1);
 
       float G[4];
       h4_t dsp;
@@ -325,7 +381,7 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float zz = (float)zp[r];
-        const float hh = (float)hfr[ct][r];
+        const float hh = (float)hown[r];
         G[r] = fmaf(q4[r], dyj, carry[r]);
         dfl = fmaf(G[r], hh - zz, dfl);
         const float u = fmaf(zz * (-kInvC * kInvC), zz, 1.f);  // 1 - tanh^2
@@ -333,27 +389,27 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
         dsp[r] = (_Float16)ds;
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) X(cur, rowb + 4 * ig + r)[col0 + jl] = dsp[r];
+      for (int r = 0; r < 4; ++r) Dx[cur * ROWS + rowb + 4 * ig + r][col0 + jl] = dsp[r];
       // dW' += H'^T dS  (this wave: all c tiles x its own j tile, rows of its row block)
 #pragma unroll
       for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = mfma_k16(hfr[c2], dsp, dWacc[c2]);
-      // dv partial over this row block:  D[*][n = j] = sum_i k_i dS[i][j]
-      {
+      {  // dv partial over this row block:  D[*][n = j] = sum_i k_i dS[i][j]
         f4_t dvv = {0.f, 0.f, 0.f, 0.f};
         dvv = mfma_k16(kfr, dsp, dvv);
-        if (lane < 16) dvP[(cur * RB + rb) * V + col0 + jl] = dvv[0];
+        if (lane < 16) dvP[(par * RB + rb) * V + col0 + jl] = dvv[0];
       }
-      // df partial: 16-lane row sums, one value per DPP row
-      {
-        const float rs = row16_sum(dfl);
-        if (jl == 0) dfP[cur * WAVES * 4 + wave * 4 + ig] = rs;
+      {  // df partial of this wave, straight to the epilogue's partial buffer
+        const float tot = wave_sum_to_lane63(dfl);
+        if (lane == 63)
+          ws.dfp[((size_t)(part * WAVES + wave) * a.B * T + (size_t)b * T + t) * N + n] = tot * kInvC;
       }
-      __syncthreads();
+      lds_barrier();
 
-      // carry = f G + dS W^T ;  dk = dS v as one more column
+      // ---- R2: carry = f G + dS W^T ;  dk = dS v as one more column
       FragT af[KS];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) af[ks] = *(const FragT *)&X(cur, rowb + jl)[FE * ig + 32 * ks];
+      for (int ks = 0; ks < KS; ++ks)
+        af[ks] = *(const FragT *)&Dx[cur * ROWS + rowb + jl][FE * ig + 32 * ks];
       f4_t d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -362,10 +418,7 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
         else
           d = mfma_k16(af[ks], wtf[ks], d);
       }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) carry[r] = fmaf(f, G[r], d[r]);
-
-      if (ct == 0) {
+      if (ct == dk_ct) {
         f4_t dkv = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -379,42 +432,25 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
           if (ws.dkh) {
             *(f4_t *)&ws.dkh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = dkv;
           } else {
-            uint2 pk;
-            pk.x = (uint32_t)f32_to_bf16(dkv[0]) | ((uint32_t)f32_to_bf16(dkv[1]) << 16);
-            pk.y = (uint32_t)f32_to_bf16(dkv[2]) | ((uint32_t)f32_to_bf16(dkv[3]) << 16);
+            uint2 p2;
+            p2.x = (uint32_t)f32_to_bf16(dkv[0]) | ((uint32_t)f32_to_bf16(dkv[1]) << 16);
+            p2.y = (uint32_t)f32_to_bf16(dkv[2]) | ((uint32_t)f32_to_bf16(dkv[3]) << 16);
             *(uint2 *)&((bf16_raw *)a.dk)[(((size_t)b * T + t) * a.Nqk + g) * K + row_base + rowb +
-                                          4 * ig] = pk;
+                                          4 * ig] = p2;
           }
         }
       }
-      if (rb == 0 && lane < 16) {  // dv: sum the row blocks of this workgroup
-        float sdv = dvP[(cur * RB + 0) * V + col0 + jl];
 #pragma unroll
-        for (int r2 = 1; r2 < RB; ++r2) sdv += dvP[(cur * RB + r2) * V + col0 + jl];
-        const size_t off = (((size_t)b * T + t) * N + n) * V + col0 + jl;
-        if constexpr (TL::P == 1)
-          ((bf16_raw *)a.dv)[off] = f32_to_bf16(sdv);
-        else
-          ws.dvp[(size_t)part * a.B * T * N * V + off] = sdv;
-      }
-      if (wave == WAVES - 1) {  // df: sum the WAVES*4 row sums in a fixed order
-        float x = lane < WAVES * 4 ? dfP[cur * WAVES * 4 + lane] : 0.f;
-        x = row16_sum(x);
-        // rows of 16 lanes -> lanes 0, 16, 32, 48 hold the four row totals
-        const float t01 = x + __shfl(x, lane ^ 16, 64);
-        const float tot = t01 + __shfl(t01, lane ^ 32, 64);
-        if (lane == 0) {
-          const float val = tot * kInvC;
-          const size_t off = ((size_t)b * T + t) * N + n;
-          if constexpr (TL::P == 1)
-            a.df[off] = val;
-          else
-            ws.dfp[(size_t)part * a.B * T * N + off] = val;
-        }
-      }
+      for (int r = 0; r < 4; ++r) carry[r] = fmaf(f, G[r], d[r]);
+      if (GROUPS == 1) finish_dv_df(par, t);
+      if (GROUPS == 2) lds_barrier();
       cur ^= 1;
     }
-    __syncthreads();  // every read of this chunk's staging and stash is done
+    if (GROUPS == 2) {
+      if (grp == 0) lds_barrier();  // let the second group finish its last step
+      finish_dv_df(0, t0);            // step s = 0 of this chunk
+    }
+    lds_barrier();  // every read of this chunk's staging, stash and partials is done
   }
 
   if (a.dH0)
@@ -431,19 +467,22 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
   }
 }
 
-// dv = bf16(sum of parts), df = sum of parts (increasing part order)
+// dv = bf16(sum of its P parts) when the state is split over workgroups;
+// df = sum of its per-wave partials.  Fixed (increasing) order in both.
 __global__ void bwd_parts_sum_kernel(const float *__restrict__ dvp, bf16_raw *__restrict__ dv,
-                                     size_t n_dv, const float *__restrict__ dfp,
-                                     float *__restrict__ df, size_t n_df, int P) {
+                                     size_t n_dv, int P, const float *__restrict__ dfp,
+                                     float *__restrict__ df, size_t n_df, int NP) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n_dv; e += stride) {
-    float s = dvp[e];
-    for (int p = 1; p < P; ++p) s += dvp[(size_t)p * n_dv + e];
-    dv[e] = f32_to_bf16(s);
+  if (P > 1) {
+    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n_dv; e += stride) {
+      float s = dvp[e];
+      for (int p = 1; p < P; ++p) s += dvp[(size_t)p * n_dv + e];
+      dv[e] = f32_to_bf16(s);
+    }
   }
   for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n_df; e += stride) {
     float s = dfp[e];
-    for (int p = 1; p < P; ++p) s += dfp[(size_t)p * n_df + e];
+    for (int p = 1; p < NP; ++p) s += dfp[(size_t)p * n_df + e];
     df[e] = s;
   }
 }
@@ -493,8 +532,9 @@ struct WsLayout {
 WsLayout bwd_ws_layout(int B, int T, int N, int Nqk, int K, int V, int P, int RB) {
   WsLayout w;
   size_t off = 0;
+  const int waves = RB * (V / 16);
   w.dvp = off; off += P > 1 ? align256((size_t)P * B * T * N * V * 4) : 0;
-  w.dfp = off; off += P > 1 ? align256((size_t)P * B * T * N * 4) : 0;
+  w.dfp = off; off += align256((size_t)P * waves * B * T * N * 4);
   w.dWp = off; off += align256((size_t)B * N * P * RB * V * V * 4);
   const size_t heads = Nqk != N ? align256((size_t)B * T * N * K * 4) : 0;
   w.dqh = off; off += heads;
@@ -525,11 +565,11 @@ hipError_t launch_bwd(const BwdArgs &a, hipStream_t s) {
                        L::BYTES, s, a, ws);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (a.T > 0) {
-      if (TL::P > 1) {
+      {
         const size_t n_dv = (size_t)a.B * a.T * a.N * a.V, n_df = (size_t)a.B * a.T * a.N;
-        hipLaunchKernelGGL(bwd_parts_sum_kernel, dim3(grid_for(n_dv, 256)), dim3(256), 0, s,
-                           (const float *)ws.dvp, (bf16_raw *)a.dv, n_dv, (const float *)ws.dfp,
-                           a.df, n_df, TL::P);
+        hipLaunchKernelGGL(bwd_parts_sum_kernel, dim3(grid_for(TL::P > 1 ? n_dv : n_df, 256)),
+                           dim3(256), 0, s, (const float *)ws.dvp, (bf16_raw *)a.dv, n_dv, TL::P,
+                           (const float *)ws.dfp, a.df, n_df, TL::P * TL::WAVES);
       }
       if (shared) {
         const size_t total = (size_t)a.B * a.T * a.Nqk * a.K;
@@ -556,10 +596,6 @@ size_t ws_bytes(int B, int T, int N, int Nqk) {
 }  // namespace
 
 int mfma_pick_rb(int K, int V, int units);
-
-#define M2RNN_TILE_CASES(X)                                                                      \
-  X(64, 64, 2) X(64, 64, 1) X(128, 128, 1) X(32, 32, 2) X(32, 32, 1) X(16, 16, 1) X(64, 16, 4)   \
-  X(64, 16, 1)
 
 hipError_t mfma_bwd(const BwdArgs &a, hipStream_t s) {
   const int rb = mfma_pick_rb(a.K, a.V, a.B * a.N);

@@ -10,6 +10,14 @@
 // fill 256 CUs; sums over rows (y, dv, df, dW) are finished across workgroups
 // in a fixed order by small epilogue kernels.
 //
+// Operand precision.  Gradients of this recurrence at T = 4096 are extremely
+// sensitive to the forward trajectory (the backward amplifies a trajectory
+// error of 2e-4 into gradient errors of several percent), so the state enters
+// its contraction as an fp16 pair (hi, lo) with hi + lo = H' to ~21 bits.  The
+// pair occupies two adjacent k-slots of the 16x16x32 MFMA and the W fragment
+// holds each row of W twice.  All other matrix-core operands (dS, the stash
+// copies of H and Z, q, k, v, dy) are single fp16 values.
+//
 // Scaled state.  tanh(x) = 1 - 2/(1 + 2^(c x)) with c = 2*log2(e).  The kernels
 // carry H' = c*H in fp32 registers, so the fp16 operand cvt(H') makes the MFMA
 // produce c*(H W) directly and the exponent needs no multiply; results that
@@ -41,6 +49,31 @@ __device__ __forceinline__ bf16_raw f32_to_bf16(float x) {
   return (bf16_raw)(u >> 16);
 }
 
+// H' -> fp16 pair packed in one dword: hi (H' truncated to 11 significant
+// bits, exact in fp16) in the low half, lo = fp16(H' - hi) in the high half.
+__device__ __forceinline__ uint32_t split_hi_lo(float h) {
+  typedef float f2_t __attribute__((ext_vector_type(2)));
+  const float hi = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, h) & 0xFFFFE000u);
+  const f2_t pr = {hi, h - hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, h2_t));
+}
+// the four hi halves of four packed pairs, as one MFMA fragment
+__device__ __forceinline__ h4_t hi_of_pairs(const uint32_t (&pk)[4]) {
+  uint2 v;
+  v.x = (pk[0] & 0xFFFFu) | (pk[1] << 16);
+  v.y = (pk[2] & 0xFFFFu) | (pk[3] << 16);
+  return __builtin_bit_cast(h4_t, v);
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains
+// the vector-memory counter, i.e. it would wait for every global load and store
+// in flight (the staged q/k/v prefetch, the per-step y / dq / dk stores) at each
+// of the one or two barriers a scan step needs.  Nothing is exchanged between
+// waves through global memory inside these kernels, so only LDS must be settled.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ f4_t mfma_k32(h8_t a, h8_t b, f4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
@@ -58,7 +91,9 @@ struct Tile {
   static constexpr int ROWS = RB * 16;         // state rows per workgroup
   static constexpr bool X32 = (V >= 32);       // 16x16x32 MFMA for the V-contraction
   static constexpr int KS = X32 ? V / 32 : 1;  // MFMAs per state contraction
-  static constexpr int LDH = V + 8;            // halfs per row of a row-major exchange buffer
+  static constexpr int LDH = V + 8;            // halfs per row of a row-major fp16 exchange buffer
+  static constexpr int LDH2 = 2 * V + 8;       // ... of a (hi, lo) pair exchange buffer
+  static constexpr int GROUPS = 1;             // >1: row-block groups run half a step apart (measured: no gain)
   static_assert(K % (16 * RB) == 0 && V % 16 == 0 && WAVES <= 16, "bad tile");
 };
 
@@ -78,5 +113,16 @@ __device__ __forceinline__ bool map_block(int units, int &unit, int &part) {
   return unit < units;
 }
 inline int grid_blocks(int units, int P) { return 8 * P * ((units + 7) / 8); }
+
+
+// (K, V, RB) tilings that are instantiated
+#define M2RNN_TILE_CASES(X)                                                                      \
+  X(64, 64, 2) X(64, 64, 1) X(128, 128, 1) X(32, 32, 2) X(32, 32, 1) X(16, 16, 1) X(64, 16, 4)   \
+  X(64, 16, 1)
+
+// (K, V) shapes of the register-resident (one wave per row block) kernels
+#define M2RNN_ROWWAVE_CASES(X)                                                                  \
+  X(16, 16) X(32, 16) X(64, 16) X(128, 16) X(16, 32) X(32, 32) X(64, 32) X(128, 32) X(16, 64)   \
+  X(32, 64) X(64, 64) X(128, 64)
 
 }  // namespace m2rnn

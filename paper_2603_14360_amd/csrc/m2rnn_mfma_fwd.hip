@@ -2,16 +2,23 @@
 //
 // Per workgroup: RB row blocks (16 rows each) of one (b, n) state, all V
 // columns, for all T steps.  Per step and wavefront (one 16 x 16 tile):
-//   1. read the fp16 copy of the row block's previous state from LDS as the
-//      MFMA A operand (all V columns: the tiles of the other waves included);
-//   2. S' = c (H W)   on the matrix cores, W fragments resident in registers;
-//   3. in registers, fp32:  s' = S' + (c k_i) v_j ; e = 2^{s'} ; r = 1/(1+e) ;
+//   R  read the row block's previous state from LDS as the MFMA A operand and
+//      run the contraction S' = c (H W); W fragments stay in registers.
+//      The state is exchanged as an fp16 pair (hi, lo) per element, hi + lo
+//      = H' to ~21 bits: the backward through this recurrence amplifies
+//      forward-trajectory errors by orders of magnitude at T = 4096, so a
+//      single fp16 operand (11 bits) is not enough.  The pair sits in adjacent
+//      k-slots of the MFMA and the W fragment repeats each row of W twice, so
+//      hi W + lo W costs one more MFMA and no extra vector-ALU work.
+//   E  in registers, fp32:  s' = S' + (c k_i) v_j ; e = 2^{s'} ; r = 1/(1+e) ;
 //      H' <- f H' + c(1-f) - 2c(1-f) r        ( = c [f H + (1-f) tanh(s)] )
-//   4. write cvt_f16(H') back to LDS for the next step (double buffered, one
-//      barrier per step);
-//   5. readout: one 16x16x16 MFMA with A = the tile just converted (k = rows)
-//      and B = q broadcast gives c * sum_i q_i H[i][j] for the tile's columns;
-//      row blocks are summed through LDS, parts through the epilogue kernel.
+//      split H' into (hi, lo), write the pair back to LDS;
+//      readout: one 16x16x16 MFMA with A = hi of the tile (k = rows) and
+//      B = q broadcast gives c * sum_i q_i H[i][j]; row blocks are summed
+//      through LDS one step later, parts through the epilogue kernel.
+// With two or more row blocks the workgroup runs them as two groups half a
+// step apart (two barriers per step): while one group waits on LDS and the
+// matrix core in R, the other keeps the vector ALU busy in E.
 // q, k, v, f for 16 steps at a time are staged through LDS; the next block's
 // global loads are in flight while the current block is computed.
 #include "m2rnn_kernels.hpp"
@@ -24,22 +31,19 @@ constexpr int TB = 16;  // steps per staging block
 
 template <typename TL>
 struct FwdSmem {
-  alignas(16) _Float16 Hx[2][TL::ROWS][TL::LDH];  // fp16 state exchange, row-major, padded rows
-  alignas(16) float kS[2][TB][TL::ROWS];          // c * k
+  alignas(16) _Float16 Hx[2][TL::ROWS][TL::LDH2];  // (hi, lo) state exchange, padded rows
+  alignas(16) float kS[2][TB][TL::ROWS];           // c * k
   alignas(16) _Float16 qS[2][TB][TL::ROWS];
   alignas(16) float vS[2][TB][TL::V];
-  alignas(16) float fS[2][TB][4];                 // f, c(1-f), -2c(1-f), unused
-  alignas(16) float yP[2][TL::RB][TL::V];         // per-row-block readout partials
+  alignas(16) float fS[2][TB][4];                  // f, c(1-f), -2c(1-f), unused
+  alignas(16) float yP[2][TL::RB][TL::V];          // per-row-block readout partials
 };
 
 template <typename TL>
 __global__ void __launch_bounds__(TL::THREADS)
     mfma_fwd_kernel(FwdArgs a, float *__restrict__ ypart_ws) {
-  constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS, KS = TL::KS;
-  constexpr int THREADS = TL::THREADS;
-  constexpr bool X32 = TL::X32;
-  constexpr int FE = X32 ? 8 : 4;  // halfs per operand fragment
-  using FragT = typename Frag<X32>::type;
+  constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS;
+  constexpr int THREADS = TL::THREADS, GROUPS = TL::GROUPS;
   constexpr int NQ = (TB * ROWS + THREADS - 1) / THREADS;
   constexpr int NV = (TB * V + THREADS - 1) / THREADS;
 
@@ -50,6 +54,7 @@ __global__ void __launch_bounds__(TL::THREADS)
   const int g = n / (N / a.Nqk);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rb = wave / CT, ct = wave - rb * CT;
+  const int grp = GROUPS == 2 ? rb / (RB / 2) : 0;
   const int jl = lane & 15, ig = lane >> 4;
   const int col0 = ct * 16, rowb = rb * 16;
   const int row_base = part * ROWS;
@@ -61,16 +66,19 @@ __global__ void __launch_bounds__(TL::THREADS)
   const bf16_raw *__restrict__ vg = (const bf16_raw *)a.v;
   const float *__restrict__ fg = a.f;
 
-  // ---- W fragments: B operand, B[k = c][n = j] = W[c][col0 + j]
-  FragT wf[KS];
+  // ---- W fragments (B operand).  k-slots 2e, 2e+1 of MFMA m both hold
+  //      W[16 m + 4 ig + e][col0 + jl]: they meet the (hi, lo) pair of that element.
+  h8_t wf[CT];
   {
     const bf16_raw *Wn = (const bf16_raw *)a.W + (size_t)n * V * V;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+    for (int m = 0; m < CT; ++m)
 #pragma unroll
-      for (int e = 0; e < FE; ++e) {
-        const int c = FE * ig + e + 32 * ks;
-        wf[ks][e] = (_Float16)bf16_to_f32(Wn[(size_t)c * V + col0 + jl]);
+      for (int e = 0; e < 4; ++e) {
+        const int c = 16 * m + 4 * ig + e;
+        const _Float16 w = (_Float16)bf16_to_f32(Wn[(size_t)c * V + col0 + jl]);
+        wf[m][2 * e] = w;
+        wf[m][2 * e + 1] = w;
       }
   }
 
@@ -82,11 +90,13 @@ __global__ void __launch_bounds__(TL::THREADS)
   if (T == 0) {
     if (a.HT)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) a.HT[st_off + (size_t)r * V] = a.H0 ? a.H0[st_off + (size_t)r * V] : 0.f;
+      for (int r = 0; r < 4; ++r)
+        a.HT[st_off + (size_t)r * V] = a.H0 ? a.H0[st_off + (size_t)r * V] : 0.f;
     return;
   }
 #pragma unroll
-  for (int r = 0; r < 4; ++r) sm.Hx[0][rowb + 4 * ig + r][col0 + jl] = (_Float16)h[r];
+  for (int r = 0; r < 4; ++r)
+    *(uint32_t *)&sm.Hx[0][rowb + 4 * ig + r][2 * (col0 + jl)] = split_hi_lo(h[r]);
 
   // ---- staging of q, k, v, f (TB steps per block)
   bf16_raw rq[NQ], rk[NQ], rv[NV];
@@ -112,6 +122,12 @@ __global__ void __launch_bounds__(TL::THREADS)
     rf = (tid < TB && t0 + tid < T) ? fg[((size_t)b * T + (t0 + tid)) * N + n] : 1.f;
   };
   auto stage_store = [&](int buf) {
+    // keep the conversions here: hoisted to the loads they would wait for the loads at once
+#pragma unroll
+    for (int m = 0; m < NQ; ++m) asm volatile("" : "+v"(rq[m]), "+v"(rk[m]));
+#pragma unroll
+    for (int m = 0; m < NV; ++m) asm volatile("" : "+v"(rv[m]));
+    asm volatile("" : "+v"(rf));
 #pragma unroll
     for (int m = 0; m < NQ; ++m) {
       const int idx = tid + m * THREADS;
@@ -139,22 +155,50 @@ __global__ void __launch_bounds__(TL::THREADS)
 
   stage_load(0);
   stage_store(0);
-  __syncthreads();
+  lds_barrier();
 
   const int nblk = (T + TB - 1) / TB;
   const int nck = (T + a.C - 1) / a.C;
   int cur = 0;
   int next_ck = 0, ck_idx = 0;
   bf16_raw *__restrict__ yg = (bf16_raw *)a.y;
+  const bool do_y = a.write_y != 0;
+
+  // final sum over the row blocks of this workgroup for step t (rb == 0 waves)
+  auto finish_y = [&](int t) {
+    if (RB > 1 && do_y && rb == 0 && jl == 0) {
+      f4_t ys = *(const f4_t *)&sm.yP[t & 1][0][col0 + 4 * ig];
+#pragma unroll
+      for (int r2 = 1; r2 < RB; ++r2) ys += *(const f4_t *)&sm.yP[t & 1][r2][col0 + 4 * ig];
+      ys *= kInvC;
+      const size_t yoff = (((size_t)b * T + t) * N + n) * V + col0 + 4 * ig;
+      if constexpr (TL::P == 1) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(ys[0]) | ((uint32_t)f32_to_bf16(ys[1]) << 16);
+        pk.y = (uint32_t)f32_to_bf16(ys[2]) | ((uint32_t)f32_to_bf16(ys[3]) << 16);
+        *(uint2 *)&yg[yoff] = pk;
+      } else {
+        *(f4_t *)&ypart_ws[(size_t)part * a.B * T * N * V + yoff] = ys;
+      }
+    }
+  };
+
+  if (GROUPS == 2 && grp == 1) lds_barrier();  // second group runs half a step behind
 
   for (int blk = 0; blk < nblk; ++blk) {
     const int t0 = blk * TB;
     const int len = (T - t0) < TB ? (T - t0) : TB;
     const int sb = blk & 1;
-    if (blk + 1 < nblk) stage_load(t0 + TB);
+    const bool more = blk + 1 < nblk;
+    if (more) stage_load(t0 + TB);
 
     for (int s = 0; s < len; ++s) {
       const int t = t0 + s;
+      // ---------------- R: contraction
+      h8_t af[CT];
+#pragma unroll
+      for (int m = 0; m < CT; ++m)
+        af[m] = *(const h8_t *)&sm.Hx[cur][rowb + jl][2 * (16 * m + 4 * ig)];
       if (a.ckpt && t == next_ck) {  // state before step t
         float *dst = a.ckpt + ((size_t)unit * nck + ck_idx) * K * V +
                      (size_t)(row_base + rowb + 4 * ig) * V + col0 + jl;
@@ -163,21 +207,20 @@ __global__ void __launch_bounds__(TL::THREADS)
         next_ck += a.C;
         ++ck_idx;
       }
-      // gate terms that do not depend on the contraction
       const float f = sm.fS[sb][s][0], gp = sm.fS[sb][s][1], m2g = sm.fS[sb][s][2];
       const f4_t k4 = *(const f4_t *)&sm.kS[sb][s][rowb + 4 * ig];
       const float vj = sm.vS[sb][s][col0 + jl];
-
+      const h4_t qf = *(const h4_t *)&sm.qS[sb][s][rowb + 4 * ig];
       f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const FragT af = *(const FragT *)&sm.Hx[cur][rowb + jl][FE * ig + 32 * ks];
-        if constexpr (X32)
-          acc = mfma_k32(af, wf[ks], acc);
-        else
-          acc = mfma_k16(af, wf[ks], acc);
-      }
-      h4_t hp;
+      for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
+      if (more && s == TB / 2) stage_store(sb ^ 1);  // next block's vectors have landed
+      if (GROUPS == 2) lds_barrier();
+
+      // ---------------- E: tanh, gate, split, write back
+      // (the other group finished the previous step's readout before the barrier above)
+      if (t > 0) finish_y(t - 1);
+      uint32_t pk[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float t1 = fmaf(f, h[r], gp);
@@ -185,44 +228,39 @@ __global__ void __launch_bounds__(TL::THREADS)
         const float e = __builtin_amdgcn_exp2f(sp);
         const float rr = __builtin_amdgcn_rcpf(1.f + e);
         h[r] = fmaf(m2g, rr, t1);
-        hp[r] = (_Float16)h[r];
+        pk[r] = split_hi_lo(h[r]);
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) sm.Hx[cur ^ 1][rowb + 4 * ig + r][col0 + jl] = hp[r];
-
-      if (a.write_y) {
-        // A[m = j][k = i] = H'[i][j] (this tile), B[k = i][n] = q_i  ->  D[m = j][*] = c y_j
-        const h4_t qf = *(const h4_t *)&sm.qS[sb][s][rowb + 4 * ig];
+      for (int r = 0; r < 4; ++r)
+        *(uint32_t *)&sm.Hx[cur ^ 1][rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+      if (do_y) {
+        // A[m = j][k = i] = hi(H'[i][j]) of this tile, B[k = i][n] = q_i -> D[m = j][*] = c y_j
+        const h4_t hp = hi_of_pairs(pk);
         f4_t yv = {0.f, 0.f, 0.f, 0.f};
         yv = mfma_k16(hp, qf, yv);
-        if (jl == 0) *(f4_t *)&sm.yP[cur][rb][col0 + 4 * ig] = yv;
-      }
-      __syncthreads();
-      if (a.write_y && rb == 0 && jl == 0) {
-        f4_t ys = *(const f4_t *)&sm.yP[cur][0][col0 + 4 * ig];
-#pragma unroll
-        for (int r2 = 1; r2 < RB; ++r2) {
-          const f4_t o = *(const f4_t *)&sm.yP[cur][r2][col0 + 4 * ig];
-          ys += o;
-        }
-        ys *= kInvC;
-        const size_t yoff = (((size_t)b * T + t) * N + n) * V + col0 + 4 * ig;
-        if constexpr (TL::P == 1) {
-          uint2 pk;
-          pk.x = (uint32_t)f32_to_bf16(ys[0]) | ((uint32_t)f32_to_bf16(ys[1]) << 16);
-          pk.y = (uint32_t)f32_to_bf16(ys[2]) | ((uint32_t)f32_to_bf16(ys[3]) << 16);
-          *(uint2 *)&yg[yoff] = pk;
-        } else {
-          *(f4_t *)&ypart_ws[(size_t)part * a.B * T * N * V + yoff] = ys;
+        if (jl == 0) {
+          if constexpr (RB > 1) {
+            *(f4_t *)&sm.yP[t & 1][rb][col0 + 4 * ig] = yv;
+          } else {
+            yv *= kInvC;
+            const size_t yoff = (((size_t)b * T + t) * N + n) * V + col0 + 4 * ig;
+            if constexpr (TL::P == 1) {
+              uint2 p2;
+              p2.x = (uint32_t)f32_to_bf16(yv[0]) | ((uint32_t)f32_to_bf16(yv[1]) << 16);
+              p2.y = (uint32_t)f32_to_bf16(yv[2]) | ((uint32_t)f32_to_bf16(yv[3]) << 16);
+              *(uint2 *)&yg[yoff] = p2;
+            } else {
+              *(f4_t *)&ypart_ws[(size_t)part * a.B * T * N * V + yoff] = yv;
+            }
+          }
         }
       }
+      lds_barrier();
       cur ^= 1;
     }
-    if (blk + 1 < nblk) {
-      stage_store(sb ^ 1);
-      __syncthreads();
-    }
   }
+  if (GROUPS == 2 && grp == 0) lds_barrier();  // let the second group finish its last step
+  finish_y(T - 1);
   if (a.HT)
 #pragma unroll
     for (int r = 0; r < 4; ++r) a.HT[st_off + (size_t)r * V] = h[r] * kInvC;
@@ -278,17 +316,10 @@ int mfma_pick_rb(int K, int V, int units) {
 
 hipError_t mfma_fwd(const FwdArgs &a, hipStream_t s) {
   const int rb = mfma_pick_rb(a.K, a.V, a.B * a.N);
-  const int key = a.K * 10000 + a.V * 10 + rb;
-  switch (key) {
-    case 64 * 10000 + 64 * 10 + 2: return launch_fwd<Tile<64, 64, 2>>(a, s);
-    case 64 * 10000 + 64 * 10 + 1: return launch_fwd<Tile<64, 64, 1>>(a, s);
-    case 128 * 10000 + 128 * 10 + 1: return launch_fwd<Tile<128, 128, 1>>(a, s);
-    case 32 * 10000 + 32 * 10 + 2: return launch_fwd<Tile<32, 32, 2>>(a, s);
-    case 32 * 10000 + 32 * 10 + 1: return launch_fwd<Tile<32, 32, 1>>(a, s);
-    case 16 * 10000 + 16 * 10 + 1: return launch_fwd<Tile<16, 16, 1>>(a, s);
-    case 64 * 10000 + 16 * 10 + 4: return launch_fwd<Tile<64, 16, 4>>(a, s);
-    case 64 * 10000 + 16 * 10 + 1: return launch_fwd<Tile<64, 16, 1>>(a, s);
-  }
+#define X(K_, V_, RB_) \
+  if (a.K == K_ && a.V == V_ && rb == RB_) return launch_fwd<Tile<K_, V_, RB_>>(a, s);
+  M2RNN_TILE_CASES(X)
+#undef X
   return hipErrorInvalidValue;
 }
 

@@ -89,7 +89,9 @@ def test_checkpoint_interval_does_not_change_results(io):
     inp = make_inputs(_small(io, 2, 75, 2, K, V, seed=17))
     ref = gu.run_oracle(inp)
     base = None
-    for chunk, use_ckpt in [(0, True), (1, True), (5, True), (16, True), (0, False)]:
+    from paper_2603_14360_amd import binding as mb
+    cmax = mb.m2rnn_max_chunk(mb.make_desc(2, 75, 2, K, V, mb.M2RNN_BF16 if io == "bf16" else mb.M2RNN_F32))
+    for chunk, use_ckpt in [(0, True), (1, True), (5, True), (min(cmax, 32), True), (0, False)]:
         print("case chunk", io, chunk, use_ckpt, flush=True)
         got = gu.run_gpu(inp, io, chunk=chunk, use_ckpt=use_ckpt)
         gu.compare(got, ref, gu.TOL[io], label="chunk=%d ckpt=%s" % (chunk, use_ckpt))
