@@ -4,44 +4,45 @@
 // The paper's kernel stores every H_t to HBM in a first pass and reloads it in
 // the reverse sweep.  Here the forward leaves one fp32 checkpoint every C steps;
 // the backward walks the chunks from last to first and, per chunk,
-//   phase A  recomputes the chunk forward from its checkpoint, parking for every
-//            step the fp16 state before the step (H'_{t-1} = c H_{t-1}) and
-//            Z'_t = c tanh(.) in an on-chip stash (LDS), and produces
-//            dq_t = H_t dy_t as one more column of the state contraction;
+//   phase A  recomputes the chunk forward from its checkpoint (same arithmetic
+//            as the forward kernel), parking for every step the fp16 state
+//            before the step (hi of H'_{t-1} = c H_{t-1}) and Z'_t = c tanh(.)
+//            in an on-chip stash (LDS);
 //   phase B  sweeps the chunk in reverse, reading the stash: no tanh and no
 //            state contraction are recomputed there.
 // Per step of phase B and wavefront (16 x 16 tile, lane = 4 rows x 1 column):
 //   G  = q_i dy_j + Ccarry                       (dL/dH_t)
-//   df += G (H'_{t-1} - Z'_t) / c                (wave + workgroup reduction)
 //   dS = (1-f) G (1 - Z^2)                       -> fp16, to LDS (row-major)
 //   dW' += H'_{t-1}^T dS       MFMA k = rows     (A = stash tiles, B = own dS)
-//   dv  = dS^T k               MFMA k = rows     (A = k broadcast)
 //   Ccarry = f G + dS W^T      MFMA k = columns  (A = dS rows from LDS, B = W^T)
-//   dk  = dS v                 one more column of that contraction
-// Row-block partials of dv, df, dW are combined in fixed order (LDS, then the
-// epilogue kernels); nothing uses atomics.
+// The per-step vectors dq_t = H_t dy_t, dk_t = dS v_t, dv_t = dS^T k_t and the
+// scalar df_t = sum G (H_{t-1} - Z_t) never leave the matrix core during a
+// chunk: each is one more MFMA whose second operand (dy_t, v_t, k_t, ones) is
+// placed in column / row (t mod chunk) only, so a 16 x 16 accumulator collects
+// the chunk's 16 steps side by side and nothing is read back per step.  At the
+// end of a phase the partial accumulators of the waves are added through LDS
+// in a fixed order and stored; nothing uses atomics.
 #include "m2rnn_kernels.hpp"
 #include "m2rnn_mfma_common.hpp"
 
 namespace m2rnn {
 namespace {
 
-constexpr int kChunkCap = 16;
+constexpr int kChunkCap = 16;  // = MFMA N: one accumulator column per step of a chunk
 
 template <typename TL>
 struct BwdLds {
   static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, LDH2 = TL::LDH2, RB = TL::RB,
                        CT = TL::CT, WAVES = TL::WAVES;
   static constexpr int X_BYTES = 2 * ROWS * LDH2 * 2;     // exchange: (hi, lo) state in phase A,
-                                                          // fp16 dS in phase B
+                                                          // fp16 dS in phase B, partials at the ends
   static constexpr int STASH_STEP = RB * CT * 64 * 8;     // one h4 per lane per tile
   static constexpr int VEC_STEP = ROWS * (4 + 4 + 2) + V * (4 + 4 + 2 + 4) + 16;
   static constexpr int PER_STEP = 2 * STASH_STEP + VEC_STEP;
-  static constexpr int PART_BYTES = 2 * RB * V * 4;
-  static constexpr int FIXED = X_BYTES + PART_BYTES;
-  static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 64) / PER_STEP;
+  static constexpr int CMAX_RAW = (kLdsLimit - X_BYTES - 64) / PER_STEP;
   static constexpr int CMAX = CMAX_RAW > kChunkCap ? kChunkCap : CMAX_RAW;
   static_assert(CMAX >= 1, "no room for a stash");
+  static_assert(X_BYTES >= 2 * WAVES * 64 * 16, "exchange buffer too small for the partials");
   // byte offsets for a stash of CMAX steps
   static constexpr int X = 0;
   static constexpr int SH = X + X_BYTES;
@@ -54,35 +55,9 @@ struct BwdLds {
   static constexpr int VH_ = KH_ + CMAX * ROWS * 2;       // half v      [C][V]
   static constexpr int DYH_ = VH_ + CMAX * V * 2;         // half dy, each value twice [C][2V]
   static constexpr int FS_ = DYH_ + CMAX * V * 4;         // float f, c(1-f), 1-f, -2c(1-f) [C][4]
-  static constexpr int DVP_ = FS_ + CMAX * 16;            // float [2][RB][V]
-  static constexpr int BYTES = DVP_ + 2 * RB * V * 4;
+  static constexpr int BYTES = FS_ + CMAX * 16;
   static_assert(BYTES <= kLdsLimit, "LDS overflow");
 };
-
-// sum over the 16 lanes of each DPP row; every lane of the row gets the total
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v) {
-  return __builtin_bit_cast(
-      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
-}
-__device__ __forceinline__ float row16_sum(float x) {
-  x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]
-  x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]
-  x += dpp_move<0x141>(x);  // row_half_mirror
-  x += dpp_move<0x140>(x);  // row_mirror
-  return x;
-}
-
-// sum over all 64 lanes; the total is valid in lane 63
-__device__ __forceinline__ float wave_sum_to_lane63(float x) {
-  x = row16_sum(x);
-  // row_bcast15 (rows 1,3 += last lane of rows 0,2), then row_bcast31 (rows 2,3 += lane 31)
-  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x142,
-                                                             0xa, 0xf, false));
-  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x143,
-                                                             0xc, 0xf, false));
-  return x;
-}
 
 struct BwdWs {
   float *dvp;   // [P][B,T,N,V]      (P > 1)
@@ -92,10 +67,17 @@ struct BwdWs {
   float *dkh;
 };
 
+__device__ __forceinline__ uint2 pack4_bf16(f4_t x) {
+  uint2 p;
+  p.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
+  p.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
+  return p;
+}
+
 template <typename TL>
 __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs ws) {
   constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS, KS = TL::KS,
-                LDH = TL::LDH, LDH2 = TL::LDH2, WAVES = TL::WAVES, GROUPS = TL::GROUPS;
+                LDH = TL::LDH, LDH2 = TL::LDH2, WAVES = TL::WAVES;
   constexpr int THREADS = TL::THREADS;
   constexpr bool X32 = TL::X32;
   constexpr int FE = X32 ? 8 : 4;
@@ -110,20 +92,21 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
   const int T = a.T, N = a.N, C = a.C;
   const int b = unit / N, n = unit - b * N;
   const int g = n / (N / a.Nqk);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // wave-level indices as scalars: branches on them must be real (uniform) branches, because
+  // a matrix-core instruction that is merely predicated off still executes
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int rb = wave / CT, ct = wave - rb * CT;
-  const int grp = GROUPS == 2 ? rb / (RB / 2) : 0;
   const int jl = lane & 15, ig = lane >> 4;
   const int col0 = ct * 16, rowb = rb * 16;
   const int row_base = part * ROWS;
-  // the per-row-block extras (dq in phase A, dk in phase B) are dealt to different waves
-  const int dq_ct = rb % CT, dk_ct = (rb + 1) % CT;
 
   extern __shared__ __attribute__((aligned(16))) char lds[];
   typedef _Float16 XRow2[LDH2];
   typedef _Float16 XRow[LDH];
   XRow2 *Hx = (XRow2 *)(lds + L::X);                // phase A view: [2*ROWS][LDH2], (hi, lo) pairs
   XRow *Dx = (XRow *)(lds + L::X);                  // phase B view: [2*ROWS][LDH], fp16 dS
+  f4_t *fin = (f4_t *)(lds + L::X);                 // phase ends: [2][WAVES][64] partial accumulators
   h4_t *stH = (h4_t *)(lds + L::SH);                // [C][RB][CT][64]
   h4_t *stZ = (h4_t *)(lds + L::SZ);
   float *kS = (float *)(lds + L::KS_);
@@ -134,7 +117,6 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
   _Float16 *vH = (_Float16 *)(lds + L::VH_);
   _Float16 *dyH = (_Float16 *)(lds + L::DYH_);
   float *fS = (float *)(lds + L::FS_);
-  float *dvP = (float *)(lds + L::DVP_);
 
   const bf16_raw *__restrict__ qg = (const bf16_raw *)a.q;
   const bf16_raw *__restrict__ kg = (const bf16_raw *)a.k;
@@ -178,6 +160,7 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
   for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = f4_t{0.f, 0.f, 0.f, 0.f};
 
   const int nck = (T + C - 1) / C;
+  const f4_t zero4 = {0.f, 0.f, 0.f, 0.f};
 
   // ---- staging: a whole chunk of q, k, v, dy, f goes through registers to LDS;
   //      the loads for chunk ck-1 are issued before phase B of chunk ck.
@@ -247,41 +230,12 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
     }
   };
 
-  // dq_t = H_t dy_t from the A fragments of H'_t = (hi, lo) pairs; B repeats dy likewise.
-  // Done by the ct == 0 wave of each row block.
-  auto emit_dq = [&](const h8_t *af, int s_prev, int t_prev) {
-    f4_t d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int m = 0; m < CT; ++m) {
-      const h8_t bf = *(const h8_t *)&dyH[s_prev * 2 * V + 2 * (16 * m + 4 * ig)];
-      d = mfma_k32(af[m], bf, d);
-    }
-    if (jl == 0) {
-      d *= kInvC;
-      if (ws.dqh) {
-        *(f4_t *)&ws.dqh[(((size_t)b * T + t_prev) * N + n) * K + row_base + rowb + 4 * ig] = d;
-      } else {
-        uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(d[0]) | ((uint32_t)f32_to_bf16(d[1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(d[2]) | ((uint32_t)f32_to_bf16(d[3]) << 16);
-        *(uint2 *)&((bf16_raw *)a.dq)[(((size_t)b * T + t_prev) * a.Nqk + g) * K + row_base +
-                                      rowb + 4 * ig] = pk;
-      }
-    }
-  };
-
-  // sums over the row blocks / waves of this workgroup for one finished step
-  auto finish_dv_df = [&](int par, int t) {
-    if (rb == 0 && lane < 16) {
-      float sdv = dvP[(par * RB + 0) * V + col0 + jl];
-#pragma unroll
-      for (int r2 = 1; r2 < RB; ++r2) sdv += dvP[(par * RB + r2) * V + col0 + jl];
-      const size_t off = (((size_t)b * T + t) * N + n) * V + col0 + jl;
-      if constexpr (TL::P == 1)
-        ((bf16_raw *)a.dv)[off] = f32_to_bf16(sdv);
-      else
-        ws.dvp[(size_t)part * a.B * T * N * V + off] = sdv;
-    }
+  // dq of chunk step s_col (= H after that step, times dy of that step): this wave adds
+  // its k-slice (columns of tile ct) into accumulator column s_col.
+  auto dq_slice = [&](f4_t acc, const h8_t &af_ct, int s_col) {
+    h8_t bf = *(const h8_t *)&dyH[s_col * 2 * V + 2 * (16 * ct + 4 * ig)];
+    if (jl != s_col) bf = h8_t{0, 0, 0, 0, 0, 0, 0, 0};
+    return mfma_k32(af_ct, bf, acc);
   };
 
   if (nck > 0) stage_load(nck - 1);
@@ -304,10 +258,10 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
     for (int r = 0; r < 4; ++r)
       *(uint32_t *)&Hx[cur * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
     lds_barrier();
-    if (GROUPS == 2 && grp == 1) lds_barrier();  // second group runs half a step behind
+    f4_t dqacc = zero4;  // D[m = i][n = s]: dq of chunk step s, this wave's k-slice
 
     for (int s = 0; s < len; ++s) {
-      // ---- R: contraction (and dq of the previous step)
+      // ---- R: contraction (and this wave's slice of dq of the previous step)
       h8_t af[CT];
 #pragma unroll
       for (int m = 0; m < CT; ++m)
@@ -315,11 +269,14 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
       const float f = fS[s * 4 + 0], gp = fS[s * 4 + 1], m2g = fS[s * 4 + 3];
       const f4_t k4 = *(const f4_t *)&kS[s * ROWS + rowb + 4 * ig];
       const float vj = vS[s * V + col0 + jl];
-      f4_t acc = {0.f, 0.f, 0.f, 0.f};
+      f4_t acc = zero4;
 #pragma unroll
       for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
-      if (ct == dq_ct && s > 0) emit_dq(af, s - 1, t0 + s - 1);
-      if (GROUPS == 2) lds_barrier();
+      if (s > 0) {  // (compile-time index per branch keeps af[] in registers)
+#pragma unroll
+        for (int m = 0; m < CT; ++m)
+          if (ct == m) dqacc = dq_slice(dqacc, af[m], s - 1);
+      }
 
       // ---- E: tanh, gate, stash, write back
       stH[((s * RB + rb) * CT + ct) * 64 + lane] = hi_of_pairs(pk);  // hi(H'_{t-1}), this tile
@@ -343,26 +300,37 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
       lds_barrier();
       cur ^= 1;
     }
-    if (GROUPS == 2 && grp == 0) lds_barrier();  // let the second group finish its last step
-    if (ct == dq_ct) {  // dq of the chunk's last step, from the state after it
-      h8_t af[CT];
+    {  // dq of the chunk's last step, from the state after it
+      const h8_t afl = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * ct + 4 * ig)];
+      dqacc = dq_slice(dqacc, afl, len - 1);
+    }
+    lds_barrier();  // all reads of the exchange buffer are done: it now carries partials
+    fin[wave * 64 + lane] = dqacc;
+    lds_barrier();
+    if (ct == 0 && jl < len) {  // lane (ig, jl): rows rowb + 4 ig + r of chunk step jl
+      f4_t d = fin[(rb * CT + 0) * 64 + lane];
 #pragma unroll
-      for (int m = 0; m < CT; ++m)
-        af[m] = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * m + 4 * ig)];
-      emit_dq(af, len - 1, t0 + len - 1);
+      for (int c2 = 1; c2 < CT; ++c2) d += fin[(rb * CT + c2) * 64 + lane];
+      d *= kInvC;
+      const int t = t0 + jl;
+      if (ws.dqh)
+        *(f4_t *)&ws.dqh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
+      else
+        *(uint2 *)&((bf16_raw *)a.dq)[(((size_t)b * T + t) * a.Nqk + g) * K + row_base + rowb +
+                                      4 * ig] = pack4_bf16(d);
     }
     lds_barrier();  // the exchange buffer is reused for dS from here on
 
     // ================= phase B: reverse sweep over the chunk
     // this chunk's vectors stay in LDS; the next chunk's are fetched into registers
     if (ck > 0) stage_load(ck - 1);
-    if (GROUPS == 2 && grp == 1) lds_barrier();
     cur = 0;
+    f4_t dkacc = zero4;  // D[m = i][n = s]   (waves ct < KS: one 32-column slice each)
+    f4_t dvacc = zero4;  // D[m = s][n = j]   partial over this row block
+    f4_t dfacc = zero4;  // D[m][n = s]       16 partial sums of df of step s
 
     for (int s = len - 1; s >= 0; --s) {
-      const int t = t0 + s;
-      const int par = s & 1;
-      // ---- E1: G, df, dS and the contractions over rows
+      // ---- E1: G, dS and the contractions over rows
       const float f = fS[s * 4 + 0], gm = fS[s * 4 + 2];
       const f4_t q4 = *(const f4_t *)&qS[s * ROWS + rowb + 4 * ig];
       const float dyj = dyS[s * V + col0 + jl];
@@ -372,8 +340,8 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
       for (int c2 = 0; c2 < CT; ++c2) hfr[c2] = stH[((s * RB + rb) * CT + c2) * 64 + lane];
       // this wave's own tile again (indexing hfr[] with the runtime ct would turn into selects)
       const h4_t hown = stH[((s * RB + rb) * CT + ct) * 64 + lane];
-      const h4_t kfr = *(const h4_t *)&kH[s * ROWS + rowb + 4 * ig];
-      if (GROUPS == 2 && s < len - 1) finish_dv_df(par ^ 1, t + 1);
+      h4_t kfr = *(const h4_t *)&kH[s * ROWS + rowb + 4 * ig];
+      const bool mine = jl == s;  // this lane's accumulator column / row belongs to step s
 
       float G[4];
       h4_t dsp;
@@ -393,24 +361,32 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
       // dW' += H'^T dS  (this wave: all c tiles x its own j tile, rows of its row block)
 #pragma unroll
       for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = mfma_k16(hfr[c2], dsp, dWacc[c2]);
-      {  // dv partial over this row block:  D[*][n = j] = sum_i k_i dS[i][j]
-        f4_t dvv = {0.f, 0.f, 0.f, 0.f};
-        dvv = mfma_k16(kfr, dsp, dvv);
-        if (lane < 16) dvP[(par * RB + rb) * V + col0 + jl] = dvv[0];
-      }
-      {  // df partial of this wave, straight to the epilogue's partial buffer
-        const float tot = wave_sum_to_lane63(dfl);
-        if (lane == 63)
-          ws.dfp[((size_t)(part * WAVES + wave) * a.B * T + (size_t)b * T + t) * N + n] = tot * kInvC;
+      // dv_s[j] = sum_i k_i dS[i][j]: A[m][k = i] = k_i in row m == s only
+      if (!mine) kfr = h4_t{0, 0, 0, 0};
+      dvacc = mfma_k16(kfr, dsp, dvacc);
+      {  // df_s = sum G (H' - Z') / c: the lane partial enters as a bf16 pair (hi, lo) in two
+         // k-slots against ones in column s; the MFMA adds the four lane groups
+        const uint32_t ub = __builtin_bit_cast(uint32_t, dfl);
+        const float lo = dfl - __builtin_bit_cast(float, ub & 0xFFFF0000u);
+        uint2 av;
+        av.x = (ub >> 16) | (__builtin_bit_cast(uint32_t, lo) & 0xFFFF0000u);
+        av.y = 0u;
+        uint2 bv;
+        bv.x = mine ? 0x3F803F80u : 0u;  // bf16 1.0 twice
+        bv.y = 0u;
+        typedef short s4_t __attribute__((ext_vector_type(4)));
+        dfacc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s4_t, av),
+                                                          __builtin_bit_cast(s4_t, bv), dfacc, 0,
+                                                          0, 0);
       }
       lds_barrier();
 
-      // ---- R2: carry = f G + dS W^T ;  dk = dS v as one more column
+      // ---- R2: carry = f G + dS W^T ;  dk_s = dS v_s into accumulator column s
       FragT af[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
         af[ks] = *(const FragT *)&Dx[cur * ROWS + rowb + jl][FE * ig + 32 * ks];
-      f4_t d = {0.f, 0.f, 0.f, 0.f};
+      f4_t d = zero4;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         if constexpr (X32)
@@ -418,39 +394,70 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
         else
           d = mfma_k16(af[ks], wtf[ks], d);
       }
-      if (ct == dk_ct) {
-        f4_t dkv = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const FragT bf = *(const FragT *)&vH[s * V + FE * ig + 32 * ks];
+      if (ct < KS) {
+        FragT bf = *(const FragT *)&vH[s * V + FE * ig + 32 * ct];
+        if (!mine) {
           if constexpr (X32)
-            dkv = mfma_k32(af[ks], bf, dkv);
+            bf = FragT{0, 0, 0, 0, 0, 0, 0, 0};
           else
-            dkv = mfma_k16(af[ks], bf, dkv);
+            bf = FragT{0, 0, 0, 0};
         }
-        if (jl == 0) {
-          if (ws.dkh) {
-            *(f4_t *)&ws.dkh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = dkv;
-          } else {
-            uint2 p2;
-            p2.x = (uint32_t)f32_to_bf16(dkv[0]) | ((uint32_t)f32_to_bf16(dkv[1]) << 16);
-            p2.y = (uint32_t)f32_to_bf16(dkv[2]) | ((uint32_t)f32_to_bf16(dkv[3]) << 16);
-            *(uint2 *)&((bf16_raw *)a.dk)[(((size_t)b * T + t) * a.Nqk + g) * K + row_base + rowb +
-                                          4 * ig] = p2;
+        // (af is indexed with a compile-time slice per branch to stay in registers)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          if (ct == ks) {
+            if constexpr (X32)
+              dkacc = mfma_k32(af[ks], bf, dkacc);
+            else
+              dkacc = mfma_k16(af[ks], bf, dkacc);
           }
-        }
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) carry[r] = fmaf(f, G[r], d[r]);
-      if (GROUPS == 1) finish_dv_df(par, t);
-      if (GROUPS == 2) lds_barrier();
       cur ^= 1;
     }
-    if (GROUPS == 2) {
-      if (grp == 0) lds_barrier();  // let the second group finish its last step
-      finish_dv_df(0, t0);            // step s = 0 of this chunk
+
+    // ---- end of the chunk: add the waves' partial accumulators through LDS and store
+    lds_barrier();  // every read of the exchange buffer, the stash and the vectors is done
+    fin[wave * 64 + lane] = dkacc;
+    fin[(WAVES + wave) * 64 + lane] = dvacc;
+    {  // df: 4 registers, then the four lane groups (lane jl of each holds step jl)
+      float x = (dfacc[0] + dfacc[1]) + (dfacc[2] + dfacc[3]);
+      x += __shfl_xor(x, 16, 64);
+      x += __shfl_xor(x, 32, 64);
+      if (lane < 16 && jl < len)
+        ws.dfp[((size_t)(part * WAVES + wave) * a.B * T + (size_t)b * T + t0 + jl) * N + n] =
+            x * kInvC;
     }
-    lds_barrier();  // every read of this chunk's staging, stash and partials is done
+    lds_barrier();
+    if (ct == 0 && jl < len) {  // dk: lane (ig, jl): rows rowb + 4 ig + r of chunk step jl
+      f4_t d = fin[(rb * CT + 0) * 64 + lane];
+#pragma unroll
+      for (int ks = 1; ks < KS; ++ks) d += fin[(rb * CT + ks) * 64 + lane];
+      const int t = t0 + jl;
+      if (ws.dkh)
+        *(f4_t *)&ws.dkh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
+      else
+        *(uint2 *)&((bf16_raw *)a.dk)[(((size_t)b * T + t) * a.Nqk + g) * K + row_base + rowb +
+                                      4 * ig] = pack4_bf16(d);
+    }
+    if (rb == 0) {  // dv: lane (ig, jl): column col0 + jl of chunk steps 4 ig + r
+      f4_t d = fin[(WAVES + 0 * CT + ct) * 64 + lane];
+#pragma unroll
+      for (int r2 = 1; r2 < RB; ++r2) d += fin[(WAVES + r2 * CT + ct) * 64 + lane];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int sc = 4 * ig + r;
+        if (sc < len) {
+          const size_t off = (((size_t)b * T + t0 + sc) * N + n) * V + col0 + jl;
+          if constexpr (TL::P == 1)
+            ((bf16_raw *)a.dv)[off] = f32_to_bf16(d[r]);
+          else
+            ws.dvp[(size_t)part * a.B * T * N * V + off] = d[r];
+        }
+      }
+    }
+    lds_barrier();  // partial buffer free; next chunk restages the vectors
   }
 
   if (a.dH0)

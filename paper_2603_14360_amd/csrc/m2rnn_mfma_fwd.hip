@@ -1,24 +1,23 @@
-// Matrix-core forward scan (Algorithm 1 of the paper; recurrence equations).
+// Matrix-core forward scan (Algorithm 1 of the paper; recurrence equations),
+// tiled variant: a 16-row block of one (b, n) state is spread over V/16 waves.
 //
-// Per workgroup: RB row blocks (16 rows each) of one (b, n) state, all V
-// columns, for all T steps.  Per step and wavefront (one 16 x 16 tile):
+// Per workgroup: RB row blocks (16 rows each) of one state, all V columns, for
+// all T steps.  Per step and wavefront (one 16 x 16 tile):
 //   R  read the row block's previous state from LDS as the MFMA A operand and
 //      run the contraction S' = c (H W); W fragments stay in registers.
 //      The state is exchanged as an fp16 pair (hi, lo) per element, hi + lo
 //      = H' to ~21 bits: the backward through this recurrence amplifies
 //      forward-trajectory errors by orders of magnitude at T = 4096, so a
 //      single fp16 operand (11 bits) is not enough.  The pair sits in adjacent
-//      k-slots of the MFMA and the W fragment repeats each row of W twice, so
-//      hi W + lo W costs one more MFMA and no extra vector-ALU work.
+//      k-slots of the MFMA and the W fragment repeats each row of W twice.
 //   E  in registers, fp32:  s' = S' + (c k_i) v_j ; e = 2^{s'} ; r = 1/(1+e) ;
 //      H' <- f H' + c(1-f) - 2c(1-f) r        ( = c [f H + (1-f) tanh(s)] )
-//      split H' into (hi, lo), write the pair back to LDS;
-//      readout: one 16x16x16 MFMA with A = hi of the tile (k = rows) and
-//      B = q broadcast gives c * sum_i q_i H[i][j]; row blocks are summed
-//      through LDS one step later, parts through the epilogue kernel.
-// With two or more row blocks the workgroup runs them as two groups half a
-// step apart (two barriers per step): while one group waits on LDS and the
-// matrix core in R, the other keeps the vector ALU busy in E.
+//      split H' into (hi, lo), write the pair back to LDS; one barrier.
+//   Y  readout without leaving the step loop: one 16x16x16 MFMA with A = hi of
+//      the tile (k = rows) and B = q placed in column (t mod 16) only.  The
+//      accumulator is kept for 16 steps, so column s of it collects
+//      c sum_i q_i H[i][j] of step s; nothing is read back per step.  Every 16
+//      steps the row blocks are summed through LDS and 16 rows of y are stored.
 // q, k, v, f for 16 steps at a time are staged through LDS; the next block's
 // global loads are in flight while the current block is computed.
 #include "m2rnn_kernels.hpp"
@@ -27,7 +26,7 @@
 namespace m2rnn {
 namespace {
 
-constexpr int TB = 16;  // steps per staging block
+constexpr int TB = 16;  // steps per staging / readout block (= MFMA N)
 
 template <typename TL>
 struct FwdSmem {
@@ -36,14 +35,14 @@ struct FwdSmem {
   alignas(16) _Float16 qS[2][TB][TL::ROWS];
   alignas(16) float vS[2][TB][TL::V];
   alignas(16) float fS[2][TB][4];                  // f, c(1-f), -2c(1-f), unused
-  alignas(16) float yP[2][TL::RB][TL::V];          // per-row-block readout partials
+  alignas(16) f4_t yB[TL::RB][TL::CT][64];         // readout accumulators of one block
 };
 
 template <typename TL>
 __global__ void __launch_bounds__(TL::THREADS)
     mfma_fwd_kernel(FwdArgs a, float *__restrict__ ypart_ws) {
   constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS;
-  constexpr int THREADS = TL::THREADS, GROUPS = TL::GROUPS;
+  constexpr int THREADS = TL::THREADS;
   constexpr int NQ = (TB * ROWS + THREADS - 1) / THREADS;
   constexpr int NV = (TB * V + THREADS - 1) / THREADS;
 
@@ -52,9 +51,11 @@ __global__ void __launch_bounds__(TL::THREADS)
   const int T = a.T, N = a.N;
   const int b = unit / N, n = unit - b * N;
   const int g = n / (N / a.Nqk);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // wave-level indices as scalars: branches on them must be real (uniform) branches, because
+  // a matrix-core instruction that is merely predicated off still executes
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int rb = wave / CT, ct = wave - rb * CT;
-  const int grp = GROUPS == 2 ? rb / (RB / 2) : 0;
   const int jl = lane & 15, ig = lane >> 4;
   const int col0 = ct * 16, rowb = rb * 16;
   const int row_base = part * ROWS;
@@ -164,33 +165,13 @@ __global__ void __launch_bounds__(TL::THREADS)
   bf16_raw *__restrict__ yg = (bf16_raw *)a.y;
   const bool do_y = a.write_y != 0;
 
-  // final sum over the row blocks of this workgroup for step t (rb == 0 waves)
-  auto finish_y = [&](int t) {
-    if (RB > 1 && do_y && rb == 0 && jl == 0) {
-      f4_t ys = *(const f4_t *)&sm.yP[t & 1][0][col0 + 4 * ig];
-#pragma unroll
-      for (int r2 = 1; r2 < RB; ++r2) ys += *(const f4_t *)&sm.yP[t & 1][r2][col0 + 4 * ig];
-      ys *= kInvC;
-      const size_t yoff = (((size_t)b * T + t) * N + n) * V + col0 + 4 * ig;
-      if constexpr (TL::P == 1) {
-        uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(ys[0]) | ((uint32_t)f32_to_bf16(ys[1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(ys[2]) | ((uint32_t)f32_to_bf16(ys[3]) << 16);
-        *(uint2 *)&yg[yoff] = pk;
-      } else {
-        *(f4_t *)&ypart_ws[(size_t)part * a.B * T * N * V + yoff] = ys;
-      }
-    }
-  };
-
-  if (GROUPS == 2 && grp == 1) lds_barrier();  // second group runs half a step behind
-
   for (int blk = 0; blk < nblk; ++blk) {
     const int t0 = blk * TB;
     const int len = (T - t0) < TB ? (T - t0) : TB;
     const int sb = blk & 1;
     const bool more = blk + 1 < nblk;
     if (more) stage_load(t0 + TB);
+    f4_t yacc = {0.f, 0.f, 0.f, 0.f};  // D[m = j][n = s] = c * y partial of step t0 + s
 
     for (int s = 0; s < len; ++s) {
       const int t = t0 + s;
@@ -210,16 +191,13 @@ __global__ void __launch_bounds__(TL::THREADS)
       const float f = sm.fS[sb][s][0], gp = sm.fS[sb][s][1], m2g = sm.fS[sb][s][2];
       const f4_t k4 = *(const f4_t *)&sm.kS[sb][s][rowb + 4 * ig];
       const float vj = sm.vS[sb][s][col0 + jl];
-      const h4_t qf = *(const h4_t *)&sm.qS[sb][s][rowb + 4 * ig];
+      h4_t qf = *(const h4_t *)&sm.qS[sb][s][rowb + 4 * ig];
       f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
       if (more && s == TB / 2) stage_store(sb ^ 1);  // next block's vectors have landed
-      if (GROUPS == 2) lds_barrier();
 
       // ---------------- E: tanh, gate, split, write back
-      // (the other group finished the previous step's readout before the barrier above)
-      if (t > 0) finish_y(t - 1);
       uint32_t pk[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -234,33 +212,40 @@ __global__ void __launch_bounds__(TL::THREADS)
       for (int r = 0; r < 4; ++r)
         *(uint32_t *)&sm.Hx[cur ^ 1][rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
       if (do_y) {
-        // A[m = j][k = i] = hi(H'[i][j]) of this tile, B[k = i][n] = q_i -> D[m = j][*] = c y_j
-        const h4_t hp = hi_of_pairs(pk);
-        f4_t yv = {0.f, 0.f, 0.f, 0.f};
-        yv = mfma_k16(hp, qf, yv);
-        if (jl == 0) {
-          if constexpr (RB > 1) {
-            *(f4_t *)&sm.yP[t & 1][rb][col0 + 4 * ig] = yv;
-          } else {
-            yv *= kInvC;
-            const size_t yoff = (((size_t)b * T + t) * N + n) * V + col0 + 4 * ig;
-            if constexpr (TL::P == 1) {
-              uint2 p2;
-              p2.x = (uint32_t)f32_to_bf16(yv[0]) | ((uint32_t)f32_to_bf16(yv[1]) << 16);
-              p2.y = (uint32_t)f32_to_bf16(yv[2]) | ((uint32_t)f32_to_bf16(yv[3]) << 16);
-              *(uint2 *)&yg[yoff] = p2;
-            } else {
-              *(f4_t *)&ypart_ws[(size_t)part * a.B * T * N * V + yoff] = yv;
-            }
-          }
-        }
+        // A[m = j][k = i] = hi(H'[i][j]) of this tile; B[k = i][n] = q_i for n == s, else 0
+        if (jl != s) qf = h4_t{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
+        yacc = mfma_k16(hi_of_pairs(pk), qf, yacc);
       }
       lds_barrier();
       cur ^= 1;
     }
+
+    if (do_y) {
+      // ---- block flush: sum the row blocks, store the block's rows of y.
+      //      Lane (ig, jl) holds columns col0 + 4 ig + r of step t0 + jl.
+      if constexpr (RB > 1) {
+        if (rb > 0) sm.yB[rb][ct][lane] = yacc;
+        lds_barrier();
+        if (rb == 0) {
+#pragma unroll
+          for (int r2 = 1; r2 < RB; ++r2) yacc += sm.yB[r2][ct][lane];
+        }
+      }
+      if (rb == 0 && jl < len) {
+        yacc *= kInvC;
+        const size_t yoff = (((size_t)b * T + t0 + jl) * N + n) * V + col0 + 4 * ig;
+        if constexpr (TL::P == 1) {
+          uint2 p2;
+          p2.x = (uint32_t)f32_to_bf16(yacc[0]) | ((uint32_t)f32_to_bf16(yacc[1]) << 16);
+          p2.y = (uint32_t)f32_to_bf16(yacc[2]) | ((uint32_t)f32_to_bf16(yacc[3]) << 16);
+          *(uint2 *)&yg[yoff] = p2;
+        } else {
+          *(f4_t *)&ypart_ws[(size_t)part * a.B * T * N * V + yoff] = yacc;
+        }
+      }
+      // (yB is written again only 16 steps, i.e. at least 16 barriers, later)
+    }
   }
-  if (GROUPS == 2 && grp == 0) lds_barrier();  // let the second group finish its last step
-  finish_y(T - 1);
   if (a.HT)
 #pragma unroll
     for (int r = 0; r < 4; ++r) a.HT[st_off + (size_t)r * V] = h[r] * kInvC;

@@ -60,7 +60,8 @@ __global__ void __launch_bounds__(RW::THREADS) rowwave_fwd_kernel(FwdArgs a) {
   const int T = a.T, N = a.N;
   const int b = unit / N, n = unit - b * N;
   const int g = n / (N / a.Nqk);
-  const int tid = threadIdx.x, lane = tid & 63, rb = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int rb = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: one row block per wave
   const int jl = lane & 15, ig = lane >> 4;
   const int row = rb * 16 + jl;  // state row of this lane
 
