@@ -272,11 +272,7 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
       f4_t acc = zero4;
 #pragma unroll
       for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
-      if (s > 0) {  // (compile-time index per branch keeps af[] in registers)
-#pragma unroll
-        for (int m = 0; m < CT; ++m)
-          if (ct == m) dqacc = dq_slice(dqacc, af[m], s - 1);
-      }
+      settle(acc);
 
       // ---- E: tanh, gate, stash, write back
       stH[((s * RB + rb) * CT + ct) * 64 + lane] = hi_of_pairs(pk);  // hi(H'_{t-1}), this tile
@@ -297,6 +293,12 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
 #pragma unroll
       for (int r = 0; r < 4; ++r)
         *(uint32_t *)&Hx[(cur ^ 1) * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+      if (s > 0) {  // dq slice of the previous step; af still holds the state after it
+                    // (compile-time index per branch keeps af[] in registers)
+#pragma unroll
+        for (int m = 0; m < CT; ++m)
+          if (ct == m) dqacc = dq_slice(dqacc, af[m], s - 1);
+      }
       lds_barrier();
       cur ^= 1;
     }
@@ -329,18 +331,33 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
     f4_t dvacc = zero4;  // D[m = s][n = j]   partial over this row block
     f4_t dfacc = zero4;  // D[m][n = s]       16 partial sums of df of step s
 
-    for (int s = len - 1; s >= 0; --s) {
-      // ---- E1: G, dS and the contractions over rows
-      const float f = fS[s * 4 + 0], gm = fS[s * 4 + 2];
-      const f4_t q4 = *(const f4_t *)&qS[s * ROWS + rowb + 4 * ig];
-      const float dyj = dyS[s * V + col0 + jl];
-      const h4_t zp = stZ[((s * RB + rb) * CT + ct) * 64 + lane];
+    // stash and vector reads of a step are issued one step ahead (they do not depend on the sweep)
+    struct StepIn {
+      float f, gm, dyj;
+      f4_t q4;
+      h4_t zp, hown, kfr;
       h4_t hfr[CT];
+    };
+    auto load_step = [&](int s) {
+      StepIn in;
+      in.f = fS[s * 4 + 0];
+      in.gm = fS[s * 4 + 2];
+      in.q4 = *(const f4_t *)&qS[s * ROWS + rowb + 4 * ig];
+      in.dyj = dyS[s * V + col0 + jl];
+      in.zp = stZ[((s * RB + rb) * CT + ct) * 64 + lane];
 #pragma unroll
-      for (int c2 = 0; c2 < CT; ++c2) hfr[c2] = stH[((s * RB + rb) * CT + c2) * 64 + lane];
+      for (int c2 = 0; c2 < CT; ++c2) in.hfr[c2] = stH[((s * RB + rb) * CT + c2) * 64 + lane];
       // this wave's own tile again (indexing hfr[] with the runtime ct would turn into selects)
-      const h4_t hown = stH[((s * RB + rb) * CT + ct) * 64 + lane];
-      h4_t kfr = *(const h4_t *)&kH[s * ROWS + rowb + 4 * ig];
+      in.hown = stH[((s * RB + rb) * CT + ct) * 64 + lane];
+      in.kfr = *(const h4_t *)&kH[s * ROWS + rowb + 4 * ig];
+      return in;
+    };
+    StepIn nxt = load_step(len - 1);
+
+    for (int s = len - 1; s >= 0; --s) {
+      // ---- E1: G and dS
+      const StepIn in = nxt;
+      const float f = in.f, gm = in.gm;
       const bool mine = jl == s;  // this lane's accumulator column / row belongs to step s
 
       float G[4];
@@ -348,9 +365,9 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
       float dfl = 0.f;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float zz = (float)zp[r];
-        const float hh = (float)hown[r];
-        G[r] = fmaf(q4[r], dyj, carry[r]);
+        const float zz = (float)in.zp[r];
+        const float hh = (float)in.hown[r];
+        G[r] = fmaf(in.q4[r], in.dyj, carry[r]);
         dfl = fmaf(G[r], hh - zz, dfl);
         const float u = fmaf(zz * (-kInvC * kInvC), zz, 1.f);  // 1 - tanh^2
         const float ds = (gm * G[r]) * u;
@@ -358,12 +375,22 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) Dx[cur * ROWS + rowb + 4 * ig + r][col0 + jl] = dsp[r];
+      if (s > 0) nxt = load_step(s - 1);
+      lds_barrier();
+
+      // ---- R2: carry = f G + dS W^T, while the matrix core also takes the row contractions
+      FragT af[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        af[ks] = *(const FragT *)&Dx[cur * ROWS + rowb + jl][FE * ig + 32 * ks];
       // dW' += H'^T dS  (this wave: all c tiles x its own j tile, rows of its row block)
 #pragma unroll
-      for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = mfma_k16(hfr[c2], dsp, dWacc[c2]);
-      // dv_s[j] = sum_i k_i dS[i][j]: A[m][k = i] = k_i in row m == s only
-      if (!mine) kfr = h4_t{0, 0, 0, 0};
-      dvacc = mfma_k16(kfr, dsp, dvacc);
+      for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = mfma_k16(in.hfr[c2], dsp, dWacc[c2]);
+      {  // dv_s[j] = sum_i k_i dS[i][j]: A[m][k = i] = k_i in row m == s only
+        h4_t kfr = in.kfr;
+        if (!mine) kfr = h4_t{0, 0, 0, 0};
+        dvacc = mfma_k16(kfr, dsp, dvacc);
+      }
       {  // df_s = sum G (H' - Z') / c: the lane partial enters as a bf16 pair (hi, lo) in two
          // k-slots against ones in column s; the MFMA adds the four lane groups
         const uint32_t ub = __builtin_bit_cast(uint32_t, dfl);
@@ -379,13 +406,6 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
                                                           __builtin_bit_cast(s4_t, bv), dfacc, 0,
                                                           0, 0);
       }
-      lds_barrier();
-
-      // ---- R2: carry = f G + dS W^T ;  dk_s = dS v_s into accumulator column s
-      FragT af[KS];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        af[ks] = *(const FragT *)&Dx[cur * ROWS + rowb + jl][FE * ig + 32 * ks];
       f4_t d = zero4;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -394,7 +414,10 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
         else
           d = mfma_k16(af[ks], wtf[ks], d);
       }
-      if (ct < KS) {
+      settle(d);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) carry[r] = fmaf(f, G[r], d[r]);
+      if (ct < KS) {  // dk_s = dS v_s into accumulator column s (one 32-column slice per wave)
         FragT bf = *(const FragT *)&vH[s * V + FE * ig + 32 * ct];
         if (!mine) {
           if constexpr (X32)
@@ -412,8 +435,6 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
               dkacc = mfma_k16(af[ks], bf, dkacc);
           }
       }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) carry[r] = fmaf(f, G[r], d[r]);
       cur ^= 1;
     }
 
@@ -464,6 +485,536 @@ __global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs 
 #pragma unroll
     for (int r = 0; r < 4; ++r) a.dH0[st_off + (size_t)r * V] = carry[r];
   // dW partial of this (unit, part, row block): rows c = 16 c2 + 4 ig + r, column col0 + jl
+  {
+    float *dst = ws.dWp + (((size_t)unit * TL::P + part) * RB + rb) * V * V;
+#pragma unroll
+    for (int c2 = 0; c2 < CT; ++c2)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        dst[(size_t)(c2 * 16 + 4 * ig + r) * V + col0 + jl] = dWacc[c2][r] * kInvC;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Overlapped variant: the recompute of chunk c-1 and the reverse sweep of chunk c
+// run at the same time in one workgroup.
+//
+// Recomputing a chunk needs only its checkpoint, so it does not have to wait
+// for the sweep of the chunk after it.  The workgroup holds two teams of WAVES
+// wavefronts: team A recomputes chunk c-1 into one half of a double-buffered
+// stash while team B sweeps chunk c out of the other half.  Both teams run
+// the same per-step code as the sequential kernel above and meet at one
+// workgroup barrier per step, which both need anyway for their own LDS
+// exchange.  The step chain of either phase is mostly LDS / barrier / MFMA
+// latency, so with twice the waves per SIMD the vector ALU is simply busy for
+// a larger share of the same time: a chunk costs about one phase, not two.
+// The stash is half as deep (two buffers), so checkpoints are twice as dense.
+template <typename TL>
+struct OvLds {
+  static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, LDH2 = TL::LDH2, RB = TL::RB,
+                       CT = TL::CT, WAVES = TL::WAVES;
+  static constexpr int HX_BYTES = 2 * ROWS * LDH2 * 2;    // team A exchange, (hi, lo) state
+  static constexpr int DX_BYTES = 2 * ROWS * LDH * 2;     // team B exchange, fp16 dS
+  static constexpr int STASH_STEP = RB * CT * 64 * 8;     // one h4 per lane per tile
+  static constexpr int VEC_A = ROWS * 4 + V * 4 + V * 4 + 16;          // c*k, v, dy twice (f16), f
+  static constexpr int VEC_B = ROWS * 4 + V * 4 + ROWS * 2 + V * 2 + 16;  // q, dy, k f16, v f16, f
+  static constexpr int PER_STEP = 4 * STASH_STEP + VEC_A + VEC_B;
+  static constexpr int FIXED = HX_BYTES + DX_BYTES;
+  static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 64) / PER_STEP;
+  static constexpr int CMAX = CMAX_RAW > 8 ? 8 : CMAX_RAW;  // two chunks share 16 accumulator columns
+  // usable: both teams fit the workgroup and the register file, the stash holds a few steps,
+  // and team B's stash half can hold its end-of-chunk partials
+  static constexpr bool OK = (2 * WAVES <= 16) && (V <= 64) && (CMAX >= 4) &&
+                             (CMAX * 2 * STASH_STEP >= 2 * WAVES * 1024) &&
+                             (HX_BYTES >= WAVES * 1024);
+  static constexpr int C_ = CMAX > 0 ? CMAX : 1;
+  static constexpr int HX = 0;
+  static constexpr int DX = HX + HX_BYTES;
+  static constexpr int ST = DX + DX_BYTES;                 // [2][ {H, Z} ][C][RB][CT][64] h4
+  static constexpr int KS_ = ST + 4 * C_ * STASH_STEP;     // team A: float c*k [C][ROWS]
+  static constexpr int VS_ = KS_ + C_ * ROWS * 4;          //         float v   [C][V]
+  static constexpr int DYH_ = VS_ + C_ * V * 4;            //         half dy twice [C][2V]
+  static constexpr int FA_ = DYH_ + C_ * V * 4;            //         float f, c(1-f), -, -2c(1-f)
+  static constexpr int QS_ = FA_ + C_ * 16;                // team B: float q   [C][ROWS]
+  static constexpr int DYS_ = QS_ + C_ * ROWS * 4;         //         float dy  [C][V]
+  static constexpr int KH_ = DYS_ + C_ * V * 4;            //         half k    [C][ROWS]
+  static constexpr int VH_ = KH_ + C_ * ROWS * 2;          //         half v    [C][V]
+  static constexpr int FB_ = VH_ + C_ * V * 2;             //         float f, -, 1-f, -
+  static constexpr int BYTES = FB_ + C_ * 16;
+  static_assert(!OK || BYTES <= kLdsLimit, "LDS overflow");
+};
+
+template <typename TL>
+__global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdArgs a, BwdWs ws) {
+  constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS, KS = TL::KS,
+                LDH = TL::LDH, LDH2 = TL::LDH2, WAVES = TL::WAVES;
+  constexpr int THREADS = TL::THREADS;  // per team
+  constexpr bool X32 = TL::X32;
+  constexpr int FE = X32 ? 8 : 4;
+  using FragT = typename Frag<X32>::type;
+  using L = OvLds<TL>;
+  constexpr int CMAX = L::C_;
+  constexpr int NQ = (CMAX * ROWS + THREADS - 1) / THREADS;
+  constexpr int NV = (CMAX * V + THREADS - 1) / THREADS;
+
+  int unit, part;
+  if (!map_block<TL::P>(a.B * a.N, unit, part)) return;
+  const int T = a.T, N = a.N, C = a.C;
+  const int b = unit / N, n = unit - b * N;
+  const int g = n / (N / a.Nqk);
+  const int lane = threadIdx.x & 63;
+  const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const bool teamA = wave_all >= WAVES;            // scalar: each team runs its own code
+  const int wave = teamA ? wave_all - WAVES : wave_all;
+  const int tid = wave * 64 + lane;                // thread index inside the team
+  const int rb = wave / CT, ct = wave - rb * CT;
+  const int jl = lane & 15, ig = lane >> 4;
+  const int col0 = ct * 16, rowb = rb * 16;
+  const int row_base = part * ROWS;
+
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  typedef _Float16 XRow2[LDH2];
+  typedef _Float16 XRow[LDH];
+  XRow2 *Hx = (XRow2 *)(lds + L::HX);
+  XRow *Dx = (XRow *)(lds + L::DX);
+  auto stH = [&](int buf) { return (h4_t *)(lds + L::ST + (buf * 2 + 0) * CMAX * L::STASH_STEP); };
+  auto stZ = [&](int buf) { return (h4_t *)(lds + L::ST + (buf * 2 + 1) * CMAX * L::STASH_STEP); };
+  float *kS = (float *)(lds + L::KS_);
+  float *vS = (float *)(lds + L::VS_);
+  _Float16 *dyH = (_Float16 *)(lds + L::DYH_);
+  float *fA = (float *)(lds + L::FA_);
+  float *qS = (float *)(lds + L::QS_);
+  float *dyS = (float *)(lds + L::DYS_);
+  _Float16 *kH = (_Float16 *)(lds + L::KH_);
+  _Float16 *vH = (_Float16 *)(lds + L::VH_);
+  float *fB = (float *)(lds + L::FB_);
+
+  const bf16_raw *__restrict__ qg = (const bf16_raw *)a.q;
+  const bf16_raw *__restrict__ kg = (const bf16_raw *)a.k;
+  const bf16_raw *__restrict__ vg = (const bf16_raw *)a.v;
+  const bf16_raw *__restrict__ dyg = (const bf16_raw *)a.dy;
+  const float *__restrict__ fg = a.f;
+  const bf16_raw *Wn = (const bf16_raw *)a.W + (size_t)n * V * V;
+
+  const size_t tile_off = (size_t)(row_base + rowb + 4 * ig) * V + col0 + jl;
+  const size_t st_off = (size_t)unit * K * V + tile_off;
+  const int nck = (T + C - 1) / C;
+  const f4_t zero4 = {0.f, 0.f, 0.f, 0.f};
+
+  if (teamA) {
+    // =====================================================================
+    // team A: recompute chunk nck-1-it into stash[it & 1], it = 0 .. nck-1
+    h8_t wf[CT];
+#pragma unroll
+    for (int m = 0; m < CT; ++m)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const _Float16 w =
+            (_Float16)bf16_to_f32(Wn[(size_t)(16 * m + 4 * ig + e) * V + col0 + jl]);
+        wf[m][2 * e] = w;
+        wf[m][2 * e + 1] = w;
+      }
+    bf16_raw rk[NQ], rv[NV], rdy[NV];
+    float rf = 1.f;
+    float hck[4];
+    auto stage_load = [&](int ck) {
+      const int t0 = ck * C;
+      const int len = (T - t0) < C ? (T - t0) : C;
+#pragma unroll
+      for (int m = 0; m < NQ; ++m) {
+        const int idx = tid + m * THREADS;
+        const int s = idx / ROWS, i = idx - s * ROWS;
+        rk[m] = s < len ? kg[(((size_t)b * T + (t0 + s)) * a.Nqk + g) * K + row_base + i]
+                        : (bf16_raw)0;
+      }
+#pragma unroll
+      for (int m = 0; m < NV; ++m) {
+        const int idx = tid + m * THREADS;
+        const int s = idx / V, j = idx - s * V;
+        const size_t off = (((size_t)b * T + (t0 + s)) * N + n) * V + j;
+        rv[m] = s < len ? vg[off] : (bf16_raw)0;
+        rdy[m] = s < len ? dyg[off] : (bf16_raw)0;
+      }
+      rf = (tid < len) ? fg[((size_t)b * T + (t0 + tid)) * N + n] : 1.f;
+      const float *src = a.ckpt + ((size_t)unit * nck + ck) * K * V + tile_off;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) hck[r] = src[(size_t)r * V];
+    };
+    auto stage_store = [&]() {
+#pragma unroll
+      for (int m = 0; m < NQ; ++m) asm volatile("" : "+v"(rk[m]));
+#pragma unroll
+      for (int m = 0; m < NV; ++m) asm volatile("" : "+v"(rv[m]), "+v"(rdy[m]));
+      asm volatile("" : "+v"(rf), "+v"(hck[0]), "+v"(hck[1]), "+v"(hck[2]), "+v"(hck[3]));
+#pragma unroll
+      for (int m = 0; m < NQ; ++m) {
+        const int idx = tid + m * THREADS;
+        if (idx < CMAX * ROWS) kS[idx] = kC * bf16_to_f32(rk[m]);
+      }
+#pragma unroll
+      for (int m = 0; m < NV; ++m) {
+        const int idx = tid + m * THREADS;
+        if (idx < CMAX * V) {
+          const float dyf = bf16_to_f32(rdy[m]);
+          vS[idx] = bf16_to_f32(rv[m]);
+          dyH[2 * idx] = (_Float16)dyf;
+          dyH[2 * idx + 1] = (_Float16)dyf;
+        }
+      }
+      if (tid < CMAX) {
+        fA[tid * 4 + 0] = rf;
+        fA[tid * 4 + 1] = kC * (1.f - rf);
+        fA[tid * 4 + 3] = -2.f * (kC * (1.f - rf));
+      }
+    };
+    auto dq_slice = [&](f4_t acc, const h8_t &af_ct, int s_col, int col) {
+      h8_t bf = *(const h8_t *)&dyH[s_col * 2 * V + 2 * (16 * ct + 4 * ig)];
+      if (jl != col) bf = h8_t{0, 0, 0, 0, 0, 0, 0, 0};
+      return mfma_k32(af_ct, bf, acc);
+    };
+
+    if (nck > 0) stage_load(nck - 1);
+    for (int it = 0; it <= nck; ++it) {
+      const bool active = it < nck;
+      const int ck = nck - 1 - it;
+      const int t0 = ck * C;
+      const int len = active ? ((T - t0) < C ? (T - t0) : C) : 0;
+      const int buf = it & 1;
+      float h[4];
+      uint32_t pk[4];
+      int cur = 0;
+      f4_t dqacc = zero4;
+      if (active) {
+        stage_store();
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          h[r] = kC * hck[r];
+          pk[r] = split_hi_lo(h[r]);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          *(uint32_t *)&Hx[cur * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+        if (ck > 0) stage_load(ck - 1);  // next chunk's vectors travel during this chunk
+      }
+      lds_barrier();  // P
+      for (int s = 0; s < C; ++s) {
+        if (s < len) {
+          h8_t af[CT];
+#pragma unroll
+          for (int m = 0; m < CT; ++m)
+            af[m] = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * m + 4 * ig)];
+          const float f = fA[s * 4 + 0], gp = fA[s * 4 + 1], m2g = fA[s * 4 + 3];
+          const f4_t k4 = *(const f4_t *)&kS[s * ROWS + rowb + 4 * ig];
+          const float vj = vS[s * V + col0 + jl];
+          f4_t acc = zero4;
+#pragma unroll
+          for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
+          settle(acc);
+          stH(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = hi_of_pairs(pk);
+          h4_t zp;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float t1 = fmaf(f, h[r], gp);
+            const float sp = fmaf(k4[r], vj, acc[r]);
+            const float e = __builtin_amdgcn_exp2f(sp);
+            const float rr = __builtin_amdgcn_rcpf(1.f + e);
+            const float z = fmaf(-2.f * kC, rr, kC);
+            h[r] = fmaf(m2g, rr, t1);
+            zp[r] = (_Float16)z;
+            pk[r] = split_hi_lo(h[r]);
+          }
+          stZ(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = zp;
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            *(uint32_t *)&Hx[(cur ^ 1) * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+          if (s > 0) {  // dq slice of the previous step; af still holds the state after it
+#pragma unroll
+            for (int m = 0; m < CT; ++m)
+              if (ct == m) dqacc = dq_slice(dqacc, af[m], s - 1, s - 1);
+          }
+          cur ^= 1;
+        }
+        lds_barrier();  // one per step, shared with team B
+      }
+      if (active) {  // dq of the chunk's last step, from the state after it
+        const h8_t afl = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * ct + 4 * ig)];
+        dqacc = dq_slice(dqacc, afl, len - 1, len - 1);
+      }
+      lds_barrier();  // E1: exchange buffer free, it carries the dq partials now
+      f4_t *fin = (f4_t *)(lds + L::HX);
+      if (active) fin[wave * 64 + lane] = dqacc;
+      lds_barrier();  // E2
+      if (active && ct == 0 && jl < len) {
+        f4_t d = fin[(rb * CT + 0) * 64 + lane];
+#pragma unroll
+        for (int c2 = 1; c2 < CT; ++c2) d += fin[(rb * CT + c2) * 64 + lane];
+        d *= kInvC;
+        const int t = t0 + jl;
+        if (ws.dqh)
+          *(f4_t *)&ws.dqh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
+        else
+          *(uint2 *)&((bf16_raw *)a.dq)[(((size_t)b * T + t) * a.Nqk + g) * K + row_base + rowb +
+                                        4 * ig] = pack4_bf16(d);
+      }
+      lds_barrier();  // E3
+    }
+    return;
+  }
+
+  // =======================================================================
+  // team B: sweep chunk nck-it out of stash[(it-1) & 1], it = 1 .. nck
+  FragT wtf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+    for (int e = 0; e < FE; ++e)
+      wtf[ks][e] = (_Float16)bf16_to_f32(Wn[(size_t)(col0 + jl) * V + FE * ig + e + 32 * ks]);
+  float carry[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) carry[r] = a.dHT ? a.dHT[st_off + (size_t)r * V] : 0.f;
+  f4_t dWacc[CT];
+#pragma unroll
+  for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = zero4;
+
+  bf16_raw rq[NQ], rk[NQ], rv[NV], rdy[NV];
+  float rf = 1.f;
+  auto stage_load = [&](int ck) {
+    const int t0 = ck * C;
+    const int len = (T - t0) < C ? (T - t0) : C;
+#pragma unroll
+    for (int m = 0; m < NQ; ++m) {
+      const int idx = tid + m * THREADS;
+      const int s = idx / ROWS, i = idx - s * ROWS;
+      const size_t off = (((size_t)b * T + (t0 + s)) * a.Nqk + g) * K + row_base + i;
+      rq[m] = s < len ? qg[off] : (bf16_raw)0;
+      rk[m] = s < len ? kg[off] : (bf16_raw)0;
+    }
+#pragma unroll
+    for (int m = 0; m < NV; ++m) {
+      const int idx = tid + m * THREADS;
+      const int s = idx / V, j = idx - s * V;
+      const size_t off = (((size_t)b * T + (t0 + s)) * N + n) * V + j;
+      rv[m] = s < len ? vg[off] : (bf16_raw)0;
+      rdy[m] = s < len ? dyg[off] : (bf16_raw)0;
+    }
+    rf = (tid < len) ? fg[((size_t)b * T + (t0 + tid)) * N + n] : 1.f;
+  };
+  auto stage_store = [&]() {
+#pragma unroll
+    for (int m = 0; m < NQ; ++m) asm volatile("" : "+v"(rq[m]), "+v"(rk[m]));
+#pragma unroll
+    for (int m = 0; m < NV; ++m) asm volatile("" : "+v"(rv[m]), "+v"(rdy[m]));
+    asm volatile("" : "+v"(rf));
+#pragma unroll
+    for (int m = 0; m < NQ; ++m) {
+      const int idx = tid + m * THREADS;
+      if (idx < CMAX * ROWS) {
+        qS[idx] = bf16_to_f32(rq[m]);
+        kH[idx] = (_Float16)bf16_to_f32(rk[m]);
+      }
+    }
+#pragma unroll
+    for (int m = 0; m < NV; ++m) {
+      const int idx = tid + m * THREADS;
+      if (idx < CMAX * V) {
+        dyS[idx] = bf16_to_f32(rdy[m]);
+        vH[idx] = (_Float16)bf16_to_f32(rv[m]);
+      }
+    }
+    if (tid < CMAX) {
+      fB[tid * 4 + 0] = rf;
+      fB[tid * 4 + 2] = 1.f - rf;
+    }
+  };
+
+  if (nck > 0) stage_load(nck - 1);
+  for (int it = 0; it <= nck; ++it) {
+    const bool active = it >= 1;
+    const int ck = nck - it;
+    const int t0 = ck * C;
+    const int len = active ? ((T - t0) < C ? (T - t0) : C) : 0;
+    const int buf = (it - 1) & 1;
+    if (active) {
+      stage_store();
+      if (ck > 0) stage_load(ck - 1);
+    }
+    lds_barrier();  // P: stash[buf] was completed by team A in the previous iteration
+    int cur = 0;
+    f4_t dkacc = zero4, dvacc = zero4, dfacc = zero4;
+    float G[4] = {0.f, 0.f, 0.f, 0.f};
+    float fprev = 0.f;
+    int sprev = 0;
+    for (int u = 0; u < C; ++u) {
+      const int s = len - 1 - u;  // chunk step of this super-step (reverse order)
+      // ---- R2 of the previous step: carry = f G + dS W^T ; dk slice
+      if (u > 0 && u <= len) {
+        FragT af[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          af[ks] = *(const FragT *)&Dx[(cur ^ 1) * ROWS + rowb + jl][FE * ig + 32 * ks];
+        f4_t d = zero4;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          if constexpr (X32)
+            d = mfma_k32(af[ks], wtf[ks], d);
+          else
+            d = mfma_k16(af[ks], wtf[ks], d);
+        }
+        settle(d);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) carry[r] = fmaf(fprev, G[r], d[r]);
+        if (ct < KS) {
+          FragT bf = *(const FragT *)&vH[sprev * V + FE * ig + 32 * ct];
+          if (jl != sprev) {
+            if constexpr (X32)
+              bf = FragT{0, 0, 0, 0, 0, 0, 0, 0};
+            else
+              bf = FragT{0, 0, 0, 0};
+          }
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            if (ct == ks) {
+              if constexpr (X32)
+                dkacc = mfma_k32(af[ks], bf, dkacc);
+              else
+                dkacc = mfma_k16(af[ks], bf, dkacc);
+            }
+        }
+      }
+      // ---- E1 of this step
+      if (u < len) {
+        const float f = fB[s * 4 + 0], gm = fB[s * 4 + 2];
+        const f4_t q4 = *(const f4_t *)&qS[s * ROWS + rowb + 4 * ig];
+        const float dyj = dyS[s * V + col0 + jl];
+        const h4_t zp = stZ(buf)[((s * RB + rb) * CT + ct) * 64 + lane];
+        h4_t hfr[CT];
+#pragma unroll
+        for (int c2 = 0; c2 < CT; ++c2) hfr[c2] = stH(buf)[((s * RB + rb) * CT + c2) * 64 + lane];
+        const h4_t hown = stH(buf)[((s * RB + rb) * CT + ct) * 64 + lane];
+        h4_t kfr = *(const h4_t *)&kH[s * ROWS + rowb + 4 * ig];
+        const bool mine = jl == s;
+        h4_t dsp;
+        float dfl = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float zz = (float)zp[r];
+          const float hh = (float)hown[r];
+          G[r] = fmaf(q4[r], dyj, carry[r]);
+          dfl = fmaf(G[r], hh - zz, dfl);
+          const float uu = fmaf(zz * (-kInvC * kInvC), zz, 1.f);
+          const float ds = (gm * G[r]) * uu;
+          dsp[r] = (_Float16)ds;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Dx[cur * ROWS + rowb + 4 * ig + r][col0 + jl] = dsp[r];
+#pragma unroll
+        for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = mfma_k16(hfr[c2], dsp, dWacc[c2]);
+        if (!mine) kfr = h4_t{0, 0, 0, 0};
+        dvacc = mfma_k16(kfr, dsp, dvacc);
+        {
+          const uint32_t ub = __builtin_bit_cast(uint32_t, dfl);
+          const float lo = dfl - __builtin_bit_cast(float, ub & 0xFFFF0000u);
+          uint2 av;
+          av.x = (ub >> 16) | (__builtin_bit_cast(uint32_t, lo) & 0xFFFF0000u);
+          av.y = 0u;
+          uint2 bv;
+          bv.x = mine ? 0x3F803F80u : 0u;
+          bv.y = 0u;
+          typedef short s4_t __attribute__((ext_vector_type(4)));
+          dfacc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s4_t, av),
+                                                            __builtin_bit_cast(s4_t, bv), dfacc,
+                                                            0, 0, 0);
+        }
+        fprev = f;
+        sprev = s;
+        cur ^= 1;
+      }
+      lds_barrier();  // one per step, shared with team A
+    }
+    // ---- R2 of the chunk's first step (the last one swept); a short chunk already ran it
+    //      inside the loop (at super-step u == len)
+    if (active && len == C) {
+      FragT af[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        af[ks] = *(const FragT *)&Dx[(cur ^ 1) * ROWS + rowb + jl][FE * ig + 32 * ks];
+      f4_t d = zero4;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        if constexpr (X32)
+          d = mfma_k32(af[ks], wtf[ks], d);
+        else
+          d = mfma_k16(af[ks], wtf[ks], d);
+      }
+      settle(d);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) carry[r] = fmaf(fprev, G[r], d[r]);
+      if (ct < KS) {
+        FragT bf = *(const FragT *)&vH[sprev * V + FE * ig + 32 * ct];
+        if (jl != sprev) {
+          if constexpr (X32)
+            bf = FragT{0, 0, 0, 0, 0, 0, 0, 0};
+          else
+            bf = FragT{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          if (ct == ks) {
+            if constexpr (X32)
+              dkacc = mfma_k32(af[ks], bf, dkacc);
+            else
+              dkacc = mfma_k16(af[ks], bf, dkacc);
+          }
+      }
+    }
+    lds_barrier();  // E1: all reads of this chunk's stash half are done: it takes the partials
+    f4_t *fin = (f4_t *)(lds + L::ST + (buf * 2) * CMAX * L::STASH_STEP);
+    if (active) {
+      fin[wave * 64 + lane] = dkacc;
+      fin[(WAVES + wave) * 64 + lane] = dvacc;
+      float x = (dfacc[0] + dfacc[1]) + (dfacc[2] + dfacc[3]);
+      x += __shfl_xor(x, 16, 64);
+      x += __shfl_xor(x, 32, 64);
+      if (lane < 16 && jl < len)
+        ws.dfp[((size_t)(part * WAVES + wave) * a.B * T + (size_t)b * T + t0 + jl) * N + n] =
+            x * kInvC;
+    }
+    lds_barrier();  // E2
+    if (active) {
+      if (ct == 0 && jl < len) {
+        f4_t d = fin[(rb * CT + 0) * 64 + lane];
+#pragma unroll
+        for (int ks = 1; ks < KS; ++ks) d += fin[(rb * CT + ks) * 64 + lane];
+        const int t = t0 + jl;
+        if (ws.dkh)
+          *(f4_t *)&ws.dkh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
+        else
+          *(uint2 *)&((bf16_raw *)a.dk)[(((size_t)b * T + t) * a.Nqk + g) * K + row_base + rowb +
+                                        4 * ig] = pack4_bf16(d);
+      }
+      if (rb == 0) {
+        f4_t d = fin[(WAVES + 0 * CT + ct) * 64 + lane];
+#pragma unroll
+        for (int r2 = 1; r2 < RB; ++r2) d += fin[(WAVES + r2 * CT + ct) * 64 + lane];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int sc = 4 * ig + r;
+          if (sc < len) {
+            const size_t off = (((size_t)b * T + t0 + sc) * N + n) * V + col0 + jl;
+            if constexpr (TL::P == 1)
+              ((bf16_raw *)a.dv)[off] = f32_to_bf16(d[r]);
+            else
+              ws.dvp[(size_t)part * a.B * T * N * V + off] = d[r];
+          }
+        }
+      }
+    }
+    lds_barrier();  // E3
+  }
+
+  if (a.dH0)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) a.dH0[st_off + (size_t)r * V] = carry[r];
   {
     float *dst = ws.dWp + (((size_t)unit * TL::P + part) * RB + rb) * V * V;
 #pragma unroll
@@ -564,12 +1115,21 @@ hipError_t launch_bwd(const BwdArgs &a, hipStream_t s) {
   ws.dkh = shared ? (float *)(a.ws + w.dkh) : nullptr;
   hipError_t e;
   if (units > 0) {
-    if (a.C > L::CMAX) return hipErrorInvalidValue;
-    e = hipFuncSetAttribute((const void *)mfma_bwd_kernel<TL>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(mfma_bwd_kernel<TL>, dim3(grid_blocks(units, TL::P)), dim3(TL::THREADS),
-                       L::BYTES, s, a, ws);
+    if constexpr (OvLds<TL>::OK) {
+      if (a.C > OvLds<TL>::CMAX) return hipErrorInvalidValue;
+      e = hipFuncSetAttribute((const void *)mfma_bwd_overlap_kernel<TL>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, OvLds<TL>::BYTES);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(mfma_bwd_overlap_kernel<TL>, dim3(grid_blocks(units, TL::P)),
+                         dim3(2 * TL::THREADS), OvLds<TL>::BYTES, s, a, ws);
+    } else {
+      if (a.C > L::CMAX) return hipErrorInvalidValue;
+      e = hipFuncSetAttribute((const void *)mfma_bwd_kernel<TL>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(mfma_bwd_kernel<TL>, dim3(grid_blocks(units, TL::P)), dim3(TL::THREADS),
+                         L::BYTES, s, a, ws);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (a.T > 0) {
       {
@@ -625,7 +1185,11 @@ size_t mfma_bwd_workspace_bytes(int B, int T, int N, int Nqk, int K, int V) {
 int mfma_bwd_max_chunk(int K, int V) {
   int best = kChunkCap;
 #define X(K_, V_, RB_) \
-  if (K == K_ && V == V_ && BwdLds<Tile<K_, V_, RB_>>::CMAX < best) best = BwdLds<Tile<K_, V_, RB_>>::CMAX;
+  if (K == K_ && V == V_) {                                                                 \
+    const int c = OvLds<Tile<K_, V_, RB_>>::OK ? OvLds<Tile<K_, V_, RB_>>::CMAX             \
+                                               : BwdLds<Tile<K_, V_, RB_>>::CMAX;           \
+    if (c < best) best = c;                                                                \
+  }
   M2RNN_TILE_CASES(X)
 #undef X
   return best;

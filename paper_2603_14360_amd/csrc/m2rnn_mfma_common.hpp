@@ -81,6 +81,14 @@ __device__ __forceinline__ f4_t mfma_k16(h4_t a, h4_t b, f4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
 }
 
+// Reads a just-finished MFMA chain's result into vector registers HERE, in the
+// basic block that issued the MFMAs.  Without it the compiler may sink the first
+// read of the result below a conditional block that follows the chain
+// (MFMA; if (...) {long block}; use): the wait states an MFMA result needs before
+// a vector-ALU read are then counted along the long path only, and the waves
+// that skip the block read the accumulator too early (seen as wrong gradients).
+__device__ __forceinline__ void settle(f4_t &d) { asm volatile("" : "+v"(d)); }
+
 template <int K_, int V_, int RB_>
 struct Tile {
   static constexpr int K = K_, V = V_, RB = RB_;

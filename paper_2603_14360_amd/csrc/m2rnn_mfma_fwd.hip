@@ -195,6 +195,7 @@ __global__ void __launch_bounds__(TL::THREADS)
       f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
+      settle(acc);
       if (more && s == TB / 2) stage_store(sb ^ 1);  // next block's vectors have landed
 
       // ---------------- E: tanh, gate, split, write back
@@ -211,13 +212,14 @@ __global__ void __launch_bounds__(TL::THREADS)
 #pragma unroll
       for (int r = 0; r < 4; ++r)
         *(uint32_t *)&sm.Hx[cur ^ 1][rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+      lds_barrier();
+      cur ^= 1;
       if (do_y) {
+        // after the barrier: the readout MFMA runs while the next step's operands are fetched.
         // A[m = j][k = i] = hi(H'[i][j]) of this tile; B[k = i][n] = q_i for n == s, else 0
         if (jl != s) qf = h4_t{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
         yacc = mfma_k16(hi_of_pairs(pk), qf, yacc);
       }
-      lds_barrier();
-      cur ^= 1;
     }
 
     if (do_y) {
@@ -286,6 +288,13 @@ hipError_t launch_fwd(const FwdArgs &a, hipStream_t s) {
 }
 
 }  // namespace
+
+void y_parts_sum_launch(const float *part, void *y, size_t total, int P, hipStream_t s) {
+  size_t blocks = (total / 4 + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(y_parts_sum_kernel, dim3((unsigned)blocks), dim3(256), 0, s, part,
+                     (bf16_raw *)y, total, P);
+}
 
 // Row blocks per workgroup for a shape: the largest tile that still gives the
 // chip at least one workgroup per CU, else the smallest tile there is.
