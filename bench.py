@@ -29,6 +29,11 @@ ALU_OPS = {"fwd": (7, 2), "bwd": (14, 2)}
 TRANS_SLOTS = 2                       # issue slots of v_exp_f32 / v_rcp_f32 relative to v_fma_f32
 PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9  # lane-ops per second, packed fp32 not used
 
+# HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs of this script
+# (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same counter reads for the
+# --calib-copy-mib copy: x2.000 and x1.000).  Summary: profiles/c3_fwd_bwd_pmc_counters.txt.
+MEASURED_TRAFFIC_BYTES = {"C3": 741355 * 1024 * 2.000 + 672153 * 1024 * 1.000}
+
 
 def alu_slots(kind):
     v, t = ALU_OPS[kind]
@@ -72,6 +77,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run a plain elementwise copy of this many MiB (read) + as many "
+                         "(write) three times before the warm-up: the yardstick that scales "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the scan has no multi-GPU path); "
@@ -99,6 +108,15 @@ def main():
         if wl.backward:
             scan.bwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"], dev["dy"],
                      dev["dHT"])
+
+    if args.calib_copy_mib > 0:
+        src = torch.ones(args.calib_copy_mib * (1 << 20) // 4, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -141,7 +159,8 @@ def main():
         "roofline": {
             "bound": "alu", "kernel": "m2rnn_%s (scan kernel of the %s call)" % (dom, dom),
             "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
-            "frac": achieved / PEAK_LANE_OPS, "traffic": None,
+            "frac": achieved / PEAK_LANE_OPS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
             "step_frac": elem_steps * step_slots / (ms_per_step * 1e-3) / PEAK_LANE_OPS,
             "fwd_frac": elem_steps * alu_slots("fwd") / (fwd_ms * 1e-3) / PEAK_LANE_OPS,
             "mfma_tflops": elem_steps * wl.V * (2 + (6 if wl.backward else 0)) / (ms_per_step * 1e-3) / 1e12,
