@@ -35,12 +35,13 @@ struct FwdSmem {
   alignas(16) _Float16 qS[2][TB][TL::ROWS];
   alignas(16) float vS[2][TB][TL::V];
   alignas(16) float fS[2][TB][4];                  // f, c(1-f), -2c(1-f), unused
-  alignas(16) f4_t yB[TL::RB][TL::CT][64];         // readout accumulators of one block
+  alignas(16) f4_t yB[TL::RB][2][TL::CT][64];      // readout accumulators of a block (by block parity)
 };
 
-template <typename TL>
+template <typename TL, bool PP, bool DO_Y>
 __global__ void __launch_bounds__(TL::THREADS)
     mfma_fwd_kernel(FwdArgs a, float *__restrict__ ypart_ws) {
+  static_assert(!PP || TL::RB == 2, "ping-pong needs two row blocks");
   constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS;
   constexpr int THREADS = TL::THREADS;
   constexpr int NQ = (TB * ROWS + THREADS - 1) / THREADS;
@@ -160,92 +161,182 @@ __global__ void __launch_bounds__(TL::THREADS)
 
   const int nblk = (T + TB - 1) / TB;
   const int nck = (T + a.C - 1) / a.C;
-  int cur = 0;
   int next_ck = 0, ck_idx = 0;
   bf16_raw *__restrict__ yg = (bf16_raw *)a.y;
-  const bool do_y = a.write_y != 0;
+  const h4_t zero_h4 = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
 
-  for (int blk = 0; blk < nblk; ++blk) {
-    const int t0 = blk * TB;
-    const int len = (T - t0) < TB ? (T - t0) : TB;
-    const int sb = blk & 1;
-    const bool more = blk + 1 < nblk;
-    if (more) stage_load(t0 + TB);
-    f4_t yacc = {0.f, 0.f, 0.f, 0.f};  // D[m = j][n = s] = c * y partial of step t0 + s
-
-    for (int s = 0; s < len; ++s) {
-      const int t = t0 + s;
-      // ---------------- R: contraction
-      h8_t af[CT];
+  // Pieces of one step.  `s` is the step inside the 16-step block; the block loop calls
+  // these from a fully unrolled loop, so s, the exchange buffer index and every LDS
+  // offset that depends on them are compile-time constants there (a wave issues one
+  // instruction every ~5 cycles at best: loop counters, address arithmetic and branches
+  // per step cost as much as the arithmetic).
+  struct StepRegs {
+    h8_t af[CT];
+    float f, gp, m2g, vj;
+    f4_t k4, acc;
+    h4_t qf;
+  };
+  auto ckpt_store = [&](int t) __attribute__((always_inline)) {
+    if (a.ckpt && t == next_ck) {  // state before step t
+      float *dst = a.ckpt + ((size_t)unit * nck + ck_idx) * K * V +
+                   (size_t)(row_base + rowb + 4 * ig) * V + col0 + jl;
 #pragma unroll
-      for (int m = 0; m < CT; ++m)
-        af[m] = *(const h8_t *)&sm.Hx[cur][rowb + jl][2 * (16 * m + 4 * ig)];
-      if (a.ckpt && t == next_ck) {  // state before step t
-        float *dst = a.ckpt + ((size_t)unit * nck + ck_idx) * K * V +
-                     (size_t)(row_base + rowb + 4 * ig) * V + col0 + jl;
+      for (int r = 0; r < 4; ++r) dst[(size_t)r * V] = h[r] * kInvC;
+      next_ck += a.C;
+      ++ck_idx;
+    }
+  };
+  // R: operand fetch from exchange buffer `buf`, this step's vectors, contraction
+  auto step_R = [&](StepRegs &x, int s, int sb, int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) dst[(size_t)r * V] = h[r] * kInvC;
-        next_ck += a.C;
-        ++ck_idx;
-      }
-      const float f = sm.fS[sb][s][0], gp = sm.fS[sb][s][1], m2g = sm.fS[sb][s][2];
-      const f4_t k4 = *(const f4_t *)&sm.kS[sb][s][rowb + 4 * ig];
-      const float vj = sm.vS[sb][s][col0 + jl];
-      h4_t qf = *(const h4_t *)&sm.qS[sb][s][rowb + 4 * ig];
-      f4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int m = 0; m < CT; ++m)
+      x.af[m] = *(const h8_t *)&sm.Hx[buf][rowb + jl][2 * (16 * m + 4 * ig)];
+    x.f = sm.fS[sb][s][0];
+    x.gp = sm.fS[sb][s][1];
+    x.m2g = sm.fS[sb][s][2];
+    x.k4 = *(const f4_t *)&sm.kS[sb][s][rowb + 4 * ig];
+    x.vj = sm.vS[sb][s][col0 + jl];
+    if constexpr (DO_Y) x.qf = *(const h4_t *)&sm.qS[sb][s][rowb + 4 * ig];
+    x.acc = f4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
-      settle(acc);
-      if (more && s == TB / 2) stage_store(sb ^ 1);  // next block's vectors have landed
-
-      // ---------------- E: tanh, gate, split, write back
-      uint32_t pk[4];
+    for (int m = 0; m < CT; ++m) x.acc = mfma_k32(x.af[m], wf[m], x.acc);
+    settle(x.acc);
+  };
+  // E: tanh, gate, split, write back into exchange buffer `buf`
+  auto step_E = [&](const StepRegs &x, uint32_t (&pk)[4], int buf) __attribute__((always_inline)) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float t1 = fmaf(f, h[r], gp);
-        const float sp = fmaf(k4[r], vj, acc[r]);
-        const float e = __builtin_amdgcn_exp2f(sp);
-        const float rr = __builtin_amdgcn_rcpf(1.f + e);
-        h[r] = fmaf(m2g, rr, t1);
-        pk[r] = split_hi_lo(h[r]);
-      }
+    for (int r = 0; r < 4; ++r) {
+      const float t1 = fmaf(x.f, h[r], x.gp);
+      const float sp = fmaf(x.k4[r], x.vj, x.acc[r]);
+      const float e = __builtin_amdgcn_exp2f(sp);
+      const float rr = __builtin_amdgcn_rcpf(1.f + e);
+      h[r] = fmaf(x.m2g, rr, t1);
+      pk[r] = split_hi_lo(h[r]);
+    }
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        *(uint32_t *)&sm.Hx[cur ^ 1][rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
-      lds_barrier();
-      cur ^= 1;
-      if (do_y) {
-        // after the barrier: the readout MFMA runs while the next step's operands are fetched.
-        // A[m = j][k = i] = hi(H'[i][j]) of this tile; B[k = i][n] = q_i for n == s, else 0
-        if (jl != s) qf = h4_t{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
-        yacc = mfma_k16(hi_of_pairs(pk), qf, yacc);
+    for (int r = 0; r < 4; ++r)
+      *(uint32_t *)&sm.Hx[buf][rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+  };
+  // Y: readout on the matrix core.  A[m = j][k = i] = hi(H'[i][j]) of this tile;
+  //    B[k = i][n] = q_i for n == s, else 0: column s of yacc collects step s.
+  auto step_Y = [&](const StepRegs &x, const uint32_t (&pk)[4], int s, f4_t &yacc)
+      __attribute__((always_inline)) {
+    const h4_t qf = (jl == s) ? x.qf : zero_h4;
+    uint2 hv;
+    hv.x = __builtin_amdgcn_perm(pk[1], pk[0], 0x05040100u);
+    hv.y = __builtin_amdgcn_perm(pk[3], pk[2], 0x05040100u);
+    yacc = mfma_k16(__builtin_bit_cast(h4_t, hv), qf, yacc);
+  };
+  auto y_store = [&](f4_t ys, int t0, int len) __attribute__((always_inline)) {
+    // lane (ig, jl) holds columns col0 + 4 ig + r of step t0 + jl
+    if (jl < len) {
+      ys *= kInvC;
+      const size_t yoff = (((size_t)b * T + t0 + jl) * N + n) * V + col0 + 4 * ig;
+      if constexpr (TL::P == 1) {
+        uint2 p2;
+        p2.x = (uint32_t)f32_to_bf16(ys[0]) | ((uint32_t)f32_to_bf16(ys[1]) << 16);
+        p2.y = (uint32_t)f32_to_bf16(ys[2]) | ((uint32_t)f32_to_bf16(ys[3]) << 16);
+        *(uint2 *)&yg[yoff] = p2;
+      } else {
+        *(f4_t *)&ypart_ws[(size_t)part * a.B * T * N * V + yoff] = ys;
       }
     }
+  };
 
-    if (do_y) {
-      // ---- block flush: sum the row blocks, store the block's rows of y.
-      //      Lane (ig, jl) holds columns col0 + 4 ig + r of step t0 + jl.
-      if constexpr (RB > 1) {
-        if (rb > 0) sm.yB[rb][ct][lane] = yacc;
+  if constexpr (PP) {
+    // ---- ping-pong schedule.  Row block 0 (waves 0..CT-1) and row block 1 run half a step
+    // apart, two barriers per step: between two barriers one row block reads its operand
+    // and runs the contraction (LDS latency, matrix core) while the other does the
+    // elementwise update and the write-back (vector ALU).  Waves w and w + CT share a
+    // SIMD, so the SIMD's vector ALU serves one of them at a time.
+    auto flush = [&](int fb) {  // row block 0's waves: add the two row blocks' y, store
+      const int ft0 = fb * TB;
+      const int flen = (T - ft0) < TB ? (T - ft0) : TB;
+      y_store(sm.yB[0][fb & 1][ct][lane] + sm.yB[1][fb & 1][ct][lane], ft0, flen);
+    };
+    int flushed = 0;             // y blocks stored so far (row block 0's waves only)
+    if (rb == 1) lds_barrier();  // row block 1 starts half a step late
+    for (int blk = 0; blk < nblk; ++blk) {
+      const int t0 = blk * TB;
+      const int len = (T - t0) < TB ? (T - t0) : TB;
+      const int sb = blk & 1;
+      const bool more = blk + 1 < nblk;
+      if (more) stage_load(t0 + TB);
+      f4_t yacc = {0.f, 0.f, 0.f, 0.f};
+      auto step = [&](int s) __attribute__((always_inline)) {
+        StepRegs x;
+        ckpt_store(t0 + s);
+        step_R(x, s, sb, 0);
+        if (s == TB / 2 && more) stage_store(sb ^ 1);
+        if (DO_Y && s == 1 && rb == 0 && flushed < blk) {  // the other row block's part of
+          flush(blk - 1);                                  // block blk-1 is visible by now
+          flushed = blk;
+        }
         lds_barrier();
-        if (rb == 0) {
+        uint32_t pk[4];
+        step_E(x, pk, 0);
+        if constexpr (DO_Y) {
+          step_Y(x, pk, s, yacc);
+          if (s == len - 1) {
+            settle(yacc);
+            sm.yB[rb][sb][ct][lane] = yacc;
+          }
+        }
+        lds_barrier();
+      };
+      if (len == TB) {
 #pragma unroll
-          for (int r2 = 1; r2 < RB; ++r2) yacc += sm.yB[r2][ct][lane];
-        }
+        for (int s = 0; s < TB; ++s) step(s);
+      } else {
+#pragma nounroll
+        for (int s = 0; s < len; ++s) step(s);
       }
-      if (rb == 0 && jl < len) {
-        yacc *= kInvC;
-        const size_t yoff = (((size_t)b * T + t0 + jl) * N + n) * V + col0 + 4 * ig;
-        if constexpr (TL::P == 1) {
-          uint2 p2;
-          p2.x = (uint32_t)f32_to_bf16(yacc[0]) | ((uint32_t)f32_to_bf16(yacc[1]) << 16);
-          p2.y = (uint32_t)f32_to_bf16(yacc[2]) | ((uint32_t)f32_to_bf16(yacc[3]) << 16);
-          *(uint2 *)&yg[yoff] = p2;
-        } else {
-          *(f4_t *)&ypart_ws[(size_t)part * a.B * T * N * V + yoff] = yacc;
-        }
+    }
+    if (rb == 0) {
+      lds_barrier();  // pairs with row block 1's last barrier: its last y block is visible
+      if constexpr (DO_Y)
+        for (int fb = flushed; fb < nblk; ++fb) flush(fb);
+    }
+  } else {
+    // ---- lock-step schedule: one barrier per step, exchange buffer alternates
+    for (int blk = 0; blk < nblk; ++blk) {
+      const int t0 = blk * TB;
+      const int len = (T - t0) < TB ? (T - t0) : TB;
+      const int sb = blk & 1;
+      const bool more = blk + 1 < nblk;
+      if (more) stage_load(t0 + TB);
+      f4_t yacc = {0.f, 0.f, 0.f, 0.f};  // D[m = j][n = s] = c * y partial of step t0 + s
+      auto step = [&](int s) __attribute__((always_inline)) {
+        StepRegs x;
+        ckpt_store(t0 + s);
+        step_R(x, s, sb, s & 1);  // every block but the last has 16 steps: parity of s
+        if (s == TB / 2 && more) stage_store(sb ^ 1);  // next block's vectors have landed
+        uint32_t pk[4];
+        step_E(x, pk, (s & 1) ^ 1);
+        lds_barrier();
+        // after the barrier: the readout MFMA runs while the next step's operands are fetched
+        if constexpr (DO_Y) step_Y(x, pk, s, yacc);
+      };
+      if (len == TB) {
+#pragma unroll
+        for (int s = 0; s < TB; ++s) step(s);
+      } else {
+#pragma nounroll
+        for (int s = 0; s < len; ++s) step(s);
       }
-      // (yB is written again only 16 steps, i.e. at least 16 barriers, later)
+      if constexpr (DO_Y) {
+        // ---- block flush: sum the row blocks, store the block's rows of y
+        if constexpr (RB > 1) {
+          if (rb > 0) sm.yB[rb][0][ct][lane] = yacc;
+          lds_barrier();
+          if (rb == 0) {
+#pragma unroll
+            for (int r2 = 1; r2 < RB; ++r2) yacc += sm.yB[r2][0][ct][lane];
+          }
+          // (yB is written again only 16 steps, i.e. at least 16 barriers, later)
+        }
+        if (rb == 0) y_store(yacc, t0, len);
+      }
     }
   }
   if (a.HT)
@@ -272,8 +363,13 @@ hipError_t launch_fwd(const FwdArgs &a, hipStream_t s) {
   const int units = a.B * a.N;
   if (units == 0) return hipSuccess;
   float *ypart = (float *)a.ws;
-  hipLaunchKernelGGL(mfma_fwd_kernel<TL>, dim3(grid_blocks(units, TL::P)), dim3(TL::THREADS), 0, s,
-                     a, ypart);
+  constexpr bool PP = false;  // (TL::RB == 2 would run the ping-pong schedule: measured slower)
+  if (a.write_y)
+    hipLaunchKernelGGL((mfma_fwd_kernel<TL, PP, true>), dim3(grid_blocks(units, TL::P)),
+                       dim3(TL::THREADS), 0, s, a, ypart);
+  else
+    hipLaunchKernelGGL((mfma_fwd_kernel<TL, PP, false>), dim3(grid_blocks(units, TL::P)),
+                       dim3(TL::THREADS), 0, s, a, ypart);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (TL::P > 1 && a.write_y && a.T > 0) {
