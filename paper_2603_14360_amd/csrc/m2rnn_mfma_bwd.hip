@@ -520,7 +520,7 @@ struct OvLds {
   static constexpr int VEC_B = ROWS * 4 + V * 4 + ROWS * 2 + V * 2 + 16;  // q, dy, k f16, v f16, f
   static constexpr int PER_STEP = 4 * STASH_STEP + VEC_A + VEC_B;
   static constexpr int FIXED = HX_BYTES + DX_BYTES;
-  static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 64) / PER_STEP;
+  static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 320) / PER_STEP;
   static constexpr int CMAX = CMAX_RAW > 8 ? 8 : CMAX_RAW;  // two chunks share 16 accumulator columns
   // usable: both teams fit the workgroup and the register file, the stash holds a few steps,
   // and team B's stash half can hold its end-of-chunk partials
@@ -530,8 +530,9 @@ struct OvLds {
   static constexpr int C_ = CMAX > 0 ? CMAX : 1;
   static constexpr int HX = 0;
   static constexpr int DX = HX + HX_BYTES;
-  static constexpr int ST = DX + DX_BYTES;                 // [2][ {H, Z} ][C][RB][CT][64] h4
-  static constexpr int KS_ = ST + 4 * C_ * STASH_STEP;     // team A: float c*k [C][ROWS]
+  // the small per-step vectors sit below the stash: their offsets then fit the 16-bit
+  // immediate of the LDS instructions (one base register instead of one per step)
+  static constexpr int KS_ = DX + DX_BYTES;                // team A: float c*k [C][ROWS]
   static constexpr int VS_ = KS_ + C_ * ROWS * 4;          //         float v   [C][V]
   static constexpr int DYH_ = VS_ + C_ * V * 4;            //         half dy twice [C][2V]
   static constexpr int FA_ = DYH_ + C_ * V * 4;            //         float f, c(1-f), -, -2c(1-f)
@@ -540,7 +541,8 @@ struct OvLds {
   static constexpr int KH_ = DYS_ + C_ * V * 4;            //         half k    [C][ROWS]
   static constexpr int VH_ = KH_ + C_ * ROWS * 2;          //         half v    [C][V]
   static constexpr int FB_ = VH_ + C_ * V * 2;             //         float f, -, 1-f, -
-  static constexpr int BYTES = FB_ + C_ * 16;
+  static constexpr int ST = (FB_ + C_ * 16 + 255) & ~255;  // [2][ {H, Z} ][C][RB][CT][64] h4
+  static constexpr int BYTES = ST + 4 * C_ * STASH_STEP;
   static_assert(!OK || BYTES <= kLdsLimit, "LDS overflow");
 };
 
@@ -697,45 +699,58 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         if (ck > 0) stage_load(ck - 1);  // next chunk's vectors travel during this chunk
       }
       lds_barrier();  // P
-      for (int s = 0; s < C; ++s) {
-        if (s < len) {
-          h8_t af[CT];
+      // one recomputed step; `s` and the exchange buffer parity are compile-time constants
+      // in the unrolled loop below (per-step loop overhead costs as much as the arithmetic)
+      auto stepA = [&](int s) __attribute__((always_inline)) {
+        const int rd = s & 1, wr = rd ^ 1;
+        h8_t af[CT];
+#pragma unroll
+        for (int m = 0; m < CT; ++m)
+          af[m] = *(const h8_t *)&Hx[rd * ROWS + rowb + jl][2 * (16 * m + 4 * ig)];
+        const float f = fA[s * 4 + 0], gp = fA[s * 4 + 1], m2g = fA[s * 4 + 3];
+        const f4_t k4 = *(const f4_t *)&kS[s * ROWS + rowb + 4 * ig];
+        const float vj = vS[s * V + col0 + jl];
+        f4_t acc = zero4;
+#pragma unroll
+        for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
+        settle(acc);
+        stH(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = hi_of_pairs(pk);
+        h4_t zp;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float t1 = fmaf(f, h[r], gp);
+          const float sp = fmaf(k4[r], vj, acc[r]);
+          const float e = __builtin_amdgcn_exp2f(sp);
+          const float rr = __builtin_amdgcn_rcpf(1.f + e);
+          const float z = fmaf(-2.f * kC, rr, kC);
+          h[r] = fmaf(m2g, rr, t1);
+          zp[r] = (_Float16)z;
+          pk[r] = split_hi_lo(h[r]);
+        }
+        stZ(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = zp;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          *(uint32_t *)&Hx[wr * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+        if (s > 0) {  // dq slice of the previous step; af still holds the state after it
 #pragma unroll
           for (int m = 0; m < CT; ++m)
-            af[m] = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * m + 4 * ig)];
-          const float f = fA[s * 4 + 0], gp = fA[s * 4 + 1], m2g = fA[s * 4 + 3];
-          const f4_t k4 = *(const f4_t *)&kS[s * ROWS + rowb + 4 * ig];
-          const float vj = vS[s * V + col0 + jl];
-          f4_t acc = zero4;
-#pragma unroll
-          for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
-          settle(acc);
-          stH(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = hi_of_pairs(pk);
-          h4_t zp;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float t1 = fmaf(f, h[r], gp);
-            const float sp = fmaf(k4[r], vj, acc[r]);
-            const float e = __builtin_amdgcn_exp2f(sp);
-            const float rr = __builtin_amdgcn_rcpf(1.f + e);
-            const float z = fmaf(-2.f * kC, rr, kC);
-            h[r] = fmaf(m2g, rr, t1);
-            zp[r] = (_Float16)z;
-            pk[r] = split_hi_lo(h[r]);
-          }
-          stZ(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = zp;
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            *(uint32_t *)&Hx[(cur ^ 1) * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
-          if (s > 0) {  // dq slice of the previous step; af still holds the state after it
-#pragma unroll
-            for (int m = 0; m < CT; ++m)
-              if (ct == m) dqacc = dq_slice(dqacc, af[m], s - 1, s - 1);
-          }
-          cur ^= 1;
+            if (ct == m) dqacc = dq_slice(dqacc, af[m], s - 1, s - 1);
         }
-        lds_barrier();  // one per step, shared with team B
+      };
+      if (C == CMAX) {
+#pragma unroll
+        for (int s = 0; s < CMAX; ++s) {
+          if (s < len) stepA(s);
+          lds_barrier();  // one per step, shared with team B
+        }
+      } else {
+#pragma nounroll
+        for (int s = 0; s < C; ++s) {
+          if (s < len) stepA(s);
+          lds_barrier();
+        }
       }
+      cur = len & 1;
       if (active) {  // dq of the chunk's last step, from the state after it
         const h8_t afl = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * ct + 4 * ig)];
         dqacc = dq_slice(dqacc, afl, len - 1, len - 1);
@@ -839,105 +854,34 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       if (ck > 0) stage_load(ck - 1);
     }
     lds_barrier();  // P: stash[buf] was completed by team A in the previous iteration
-    int cur = 0;
     f4_t dkacc = zero4, dvacc = zero4, dfacc = zero4;
     float G[4] = {0.f, 0.f, 0.f, 0.f};
     float fprev = 0.f;
-    int sprev = 0;
-    for (int u = 0; u < C; ++u) {
-      const int s = len - 1 - u;  // chunk step of this super-step (reverse order)
-      // ---- R2 of the previous step: carry = f G + dS W^T ; dk slice
-      if (u > 0 && u <= len) {
-        FragT af[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          af[ks] = *(const FragT *)&Dx[(cur ^ 1) * ROWS + rowb + jl][FE * ig + 32 * ks];
-        f4_t d = zero4;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          if constexpr (X32)
-            d = mfma_k32(af[ks], wtf[ks], d);
-          else
-            d = mfma_k16(af[ks], wtf[ks], d);
-        }
-        settle(d);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) carry[r] = fmaf(fprev, G[r], d[r]);
-        if (ct < KS) {
-          FragT bf = *(const FragT *)&vH[sprev * V + FE * ig + 32 * ct];
-          if (jl != sprev) {
-            if constexpr (X32)
-              bf = FragT{0, 0, 0, 0, 0, 0, 0, 0};
-            else
-              bf = FragT{0, 0, 0, 0};
-          }
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks)
-            if (ct == ks) {
-              if constexpr (X32)
-                dkacc = mfma_k32(af[ks], bf, dkacc);
-              else
-                dkacc = mfma_k16(af[ks], bf, dkacc);
-            }
-        }
-      }
-      // ---- E1 of this step
-      if (u < len) {
-        const float f = fB[s * 4 + 0], gm = fB[s * 4 + 2];
-        const f4_t q4 = *(const f4_t *)&qS[s * ROWS + rowb + 4 * ig];
-        const float dyj = dyS[s * V + col0 + jl];
-        const h4_t zp = stZ(buf)[((s * RB + rb) * CT + ct) * 64 + lane];
-        h4_t hfr[CT];
-#pragma unroll
-        for (int c2 = 0; c2 < CT; ++c2) hfr[c2] = stH(buf)[((s * RB + rb) * CT + c2) * 64 + lane];
-        const h4_t hown = stH(buf)[((s * RB + rb) * CT + ct) * 64 + lane];
-        h4_t kfr = *(const h4_t *)&kH[s * ROWS + rowb + 4 * ig];
-        const bool mine = jl == s;
-        h4_t dsp;
-        float dfl = 0.f;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float zz = (float)zp[r];
-          const float hh = (float)hown[r];
-          G[r] = fmaf(q4[r], dyj, carry[r]);
-          dfl = fmaf(G[r], hh - zz, dfl);
-          const float uu = fmaf(zz * (-kInvC * kInvC), zz, 1.f);
-          const float ds = (gm * G[r]) * uu;
-          dsp[r] = (_Float16)ds;
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) Dx[cur * ROWS + rowb + 4 * ig + r][col0 + jl] = dsp[r];
-#pragma unroll
-        for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = mfma_k16(hfr[c2], dsp, dWacc[c2]);
-        if (!mine) kfr = h4_t{0, 0, 0, 0};
-        dvacc = mfma_k16(kfr, dsp, dvacc);
-        {
-          const uint32_t ub = __builtin_bit_cast(uint32_t, dfl);
-          const float lo = dfl - __builtin_bit_cast(float, ub & 0xFFFF0000u);
-          uint2 av;
-          av.x = (ub >> 16) | (__builtin_bit_cast(uint32_t, lo) & 0xFFFF0000u);
-          av.y = 0u;
-          uint2 bv;
-          bv.x = mine ? 0x3F803F80u : 0u;
-          bv.y = 0u;
-          typedef short s4_t __attribute__((ext_vector_type(4)));
-          dfacc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s4_t, av),
-                                                            __builtin_bit_cast(s4_t, bv), dfacc,
-                                                            0, 0, 0);
-        }
-        fprev = f;
-        sprev = s;
-        cur ^= 1;
-      }
-      lds_barrier();  // one per step, shared with team A
-    }
-    // ---- R2 of the chunk's first step (the last one swept); a short chunk already ran it
-    //      inside the loop (at super-step u == len)
-    if (active && len == C) {
+    // LDS addressing of this team: a few per-lane base offsets, made opaque once per chunk so
+    // that they are not hoisted out of the chunk loop as one register per (array, step);
+    // every access below is base + compile-time immediate in the unrolled sweep.
+    constexpr int HALF = 2 * CMAX * L::STASH_STEP;  // one stash buffer: H part, then Z part
+    lchar *const l0 = (lchar *)lds;
+    lchar *bH = l0 + (L::ST + buf * HALF + rb * CT * 512 + lane * 8);  // stash H, tile 0 of my row block
+    lchar *bO = bH + ct * 512;                                // my own tile (H; Z at + CMAX steps)
+    lchar *bR4 = l0 + (rowb + 4 * ig) * 4;                    // q rows (fp32)
+    lchar *bR2 = l0 + (rowb + 4 * ig) * 2;                    // k rows (fp16)
+    lchar *bC4 = l0 + (col0 + jl) * 4;                        // dy column (fp32)
+    lchar *bDw = l0 + ((rowb + 4 * ig) * LDH + col0 + jl) * 2;  // dS write
+    lchar *bDr = l0 + ((rowb + jl) * LDH + FE * ig) * 2;      // dS fragment read
+    lchar *bV = l0 + (FE * ig + 32 * ct) * 2;                 // v slice of the dk MFMA
+    lchar *bZero = l0;                                        // wave-uniform reads (f)
+    int jlB = jl;  // opaque as well: the per-step column masks (jl == s) are then built per
+                   // step instead of being kept in registers for every s of an unrolled sweep
+    asm volatile("" : "+v"(bH), "+v"(bO), "+v"(bR4), "+v"(bR2), "+v"(bC4), "+v"(bDw), "+v"(bDr),
+                 "+v"(bV), "+v"(bZero), "+v"(jlB));
+    // R2 of chunk step sp (swept one super-step earlier): carry = f G + dS W^T ; dk slice.
+    // Its dS is in exchange buffer `rd`.
+    auto R2 = [&](int sp, int rd) __attribute__((always_inline)) {
       FragT af[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        af[ks] = *(const FragT *)&Dx[(cur ^ 1) * ROWS + rowb + jl][FE * ig + 32 * ks];
+        af[ks] = lds_ld<FragT>(bDr, L::DX + rd * ROWS * LDH * 2 + 32 * ks * 2);
       f4_t d = zero4;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -950,8 +894,8 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
 #pragma unroll
       for (int r = 0; r < 4; ++r) carry[r] = fmaf(fprev, G[r], d[r]);
       if (ct < KS) {
-        FragT bf = *(const FragT *)&vH[sprev * V + FE * ig + 32 * ct];
-        if (jl != sprev) {
+        FragT bf = lds_ld<FragT>(bV, L::VH_ + sp * V * 2);
+        if (jlB != sp) {
           if constexpr (X32)
             bf = FragT{0, 0, 0, 0, 0, 0, 0, 0};
           else
@@ -966,6 +910,75 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
               dkacc = mfma_k16(af[ks], bf, dkacc);
           }
       }
+    };
+    // E1 of chunk step s: G, df partial, dS into exchange buffer `wr`, row contractions
+    auto E1 = [&](int s, int wr) __attribute__((always_inline)) {
+      const float f = lds_ld<float>(bZero, L::FB_ + s * 16 + 0);
+      const float gm = lds_ld<float>(bZero, L::FB_ + s * 16 + 8);
+      const f4_t q4 = lds_ld<f4_t>(bR4, L::QS_ + s * ROWS * 4);
+      const float dyj = lds_ld<float>(bC4, L::DYS_ + s * V * 4);
+      const h4_t zp = lds_ld<h4_t>(bO, (CMAX + s) * L::STASH_STEP);
+      h4_t hfr[CT];
+#pragma unroll
+      for (int c2 = 0; c2 < CT; ++c2)
+        hfr[c2] = lds_ld<h4_t>(bH, s * L::STASH_STEP + c2 * 512);
+      const h4_t hown = lds_ld<h4_t>(bO, s * L::STASH_STEP);
+      h4_t kfr = lds_ld<h4_t>(bR2, L::KH_ + s * ROWS * 2);
+      const bool mine = jlB == s;
+      // H' - Z' and 1 - tanh^2 in packed fp16 (their inputs are fp16 stash values, so fp32
+      // would add nothing); G, the df sum and dS = (1-f) G (1 - tanh^2) in fp32 with the
+      // fp16 factors converted inside the multiply-add
+      const h4_t one4 = {(_Float16)1.f, (_Float16)1.f, (_Float16)1.f, (_Float16)1.f};
+      const h4_t hz = hown - zp;
+      const h4_t uu = (zp * (_Float16)(-kInvC * kInvC)) * zp + one4;
+      h4_t dsp;
+      float dfl = 0.f;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        G[r] = fmaf(q4[r], dyj, carry[r]);
+        dfl = fmaf(G[r], (float)hz[r], dfl);
+        dsp[r] = (_Float16)((gm * G[r]) * (float)uu[r]);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        lds_st<_Float16>(bDw, L::DX + (wr * ROWS + r) * LDH * 2, dsp[r]);
+#pragma unroll
+      for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = mfma_k16(hfr[c2], dsp, dWacc[c2]);
+      if (!mine) kfr = h4_t{0, 0, 0, 0};
+      dvacc = mfma_k16(kfr, dsp, dvacc);
+      {
+        const uint32_t ub = __builtin_bit_cast(uint32_t, dfl);
+        const float lo = dfl - __builtin_bit_cast(float, ub & 0xFFFF0000u);
+        uint2 av;
+        av.x = (ub >> 16) | (__builtin_bit_cast(uint32_t, lo) & 0xFFFF0000u);
+        av.y = 0u;
+        uint2 bv;
+        bv.x = mine ? 0x3F803F80u : 0u;
+        bv.y = 0u;
+        typedef short s4_t __attribute__((ext_vector_type(4)));
+        dfacc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s4_t, av),
+                                                          __builtin_bit_cast(s4_t, bv), dfacc,
+                                                          0, 0, 0);
+      }
+      fprev = f;
+    };
+    {
+      // (a fully unrolled sweep with compile-time step indices was measured 20 % slower
+      //  than this loop, unlike the recompute team's and the forward kernel's)
+      int cur = 0, sprev = 0;
+#pragma nounroll
+      for (int u = 0; u < C; ++u) {
+        const int s = len - 1 - u;  // chunk step of this super-step (reverse order)
+        if (u > 0 && u <= len) R2(sprev, cur ^ 1);
+        if (u < len) {
+          E1(s, cur);
+          sprev = s;
+          cur ^= 1;
+        }
+        lds_barrier();
+      }
+      // R2 of the chunk's first step; a short chunk already ran it at super-step u == len
+      if (active && len == C) R2(sprev, cur ^ 1);
     }
     lds_barrier();  // E1: all reads of this chunk's stash half are done: it takes the partials
     f4_t *fin = (f4_t *)(lds + L::ST + (buf * 2) * CMAX * L::STASH_STEP);

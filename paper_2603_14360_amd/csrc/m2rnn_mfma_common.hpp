@@ -74,6 +74,18 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// LDS access as base register + compile-time byte offset (the offset lands in the
+// instruction's 16-bit immediate).  `lchar` pointers are 32-bit LDS addresses.
+typedef __attribute__((address_space(3))) char lchar;
+template <typename T>
+__device__ __forceinline__ T lds_ld(const lchar *p, int off) {
+  return *(const __attribute__((address_space(3))) T *)(p + off);
+}
+template <typename T>
+__device__ __forceinline__ void lds_st(lchar *p, int off, T v) {
+  *(__attribute__((address_space(3))) T *)(p + off) = v;
+}
+
 __device__ __forceinline__ f4_t mfma_k32(h8_t a, h8_t b, f4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
