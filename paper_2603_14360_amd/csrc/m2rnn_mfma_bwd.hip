@@ -520,7 +520,7 @@ struct OvLds {
   static constexpr int VEC_B = ROWS * 4 + V * 4 + ROWS * 2 + V * 2 + 16;  // q, dy, k f16, v f16, f
   static constexpr int PER_STEP = 4 * STASH_STEP + VEC_A + VEC_B;
   static constexpr int FIXED = HX_BYTES + DX_BYTES;
-  static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 320) / PER_STEP;
+  static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 352) / PER_STEP;
   static constexpr int CMAX = CMAX_RAW > 8 ? 8 : CMAX_RAW;  // two chunks share 16 accumulator columns
   // usable: both teams fit the workgroup and the register file, the stash holds a few steps,
   // and team B's stash half can hold its end-of-chunk partials
@@ -540,8 +540,9 @@ struct OvLds {
   static constexpr int DYS_ = QS_ + C_ * ROWS * 4;         //         float dy  [C][V]
   static constexpr int KH_ = DYS_ + C_ * V * 4;            //         half k    [C][ROWS]
   static constexpr int VH_ = KH_ + C_ * ROWS * 2;          //         half v    [C][V]
-  static constexpr int FB_ = VH_ + C_ * V * 2;             //         float f, -, 1-f, -
-  static constexpr int ST = (FB_ + C_ * 16 + 255) & ~255;  // [2][ {H, Z} ][C][RB][CT][64] h4
+  static constexpr int FB_ = VH_ + C_ * V * 2;             //         f; f16x2 -(1-f)/c^2; f16x2 (1-f); -
+  static constexpr int ZERO_ = FB_ + C_ * 16;              // 32 zero bytes (masked operand reads)
+  static constexpr int ST = (ZERO_ + 32 + 255) & ~255;     // [2][ {H, Z} ][C][RB][CT][64] h4
   static constexpr int BYTES = ST + 4 * C_ * STASH_STEP;
   static_assert(!OK || BYTES <= kLdsLimit, "LDS overflow");
 };
@@ -602,6 +603,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   const size_t st_off = (size_t)unit * K * V + tile_off;
   const int nck = (T + C - 1) / C;
   const f4_t zero4 = {0.f, 0.f, 0.f, 0.f};
+  if (threadIdx.x < 8) ((uint32_t *)(lds + L::ZERO_))[threadIdx.x] = 0u;  // visible after barrier P
 
   if (teamA) {
     // =====================================================================
@@ -837,8 +839,12 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       }
     }
     if (tid < CMAX) {
+      const float gm = 1.f - rf;
+      const h2_t m2 = {(_Float16)(gm * (-kInvC * kInvC)), (_Float16)(gm * (-kInvC * kInvC))};
+      const h2_t g2 = {(_Float16)gm, (_Float16)gm};
       fB[tid * 4 + 0] = rf;
-      fB[tid * 4 + 2] = 1.f - rf;
+      fB[tid * 4 + 1] = __builtin_bit_cast(float, m2);
+      fB[tid * 4 + 2] = __builtin_bit_cast(float, g2);
     }
   };
 
@@ -894,13 +900,8 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
 #pragma unroll
       for (int r = 0; r < 4; ++r) carry[r] = fmaf(fprev, G[r], d[r]);
       if (ct < KS) {
-        FragT bf = lds_ld<FragT>(bV, L::VH_ + sp * V * 2);
-        if (jlB != sp) {
-          if constexpr (X32)
-            bf = FragT{0, 0, 0, 0, 0, 0, 0, 0};
-          else
-            bf = FragT{0, 0, 0, 0};
-        }
+        // v_s in column sp of the B operand only: the other lanes read zeros
+        const FragT bf = lds_ld<FragT>(jlB == sp ? bV + (L::VH_ + sp * V * 2) : bZero + L::ZERO_, 0);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
           if (ct == ks) {
@@ -913,8 +914,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     };
     // E1 of chunk step s: G, df partial, dS into exchange buffer `wr`, row contractions
     auto E1 = [&](int s, int wr) __attribute__((always_inline)) {
-      const float f = lds_ld<float>(bZero, L::FB_ + s * 16 + 0);
-      const float gm = lds_ld<float>(bZero, L::FB_ + s * 16 + 8);
+      const u4_t fu = lds_ld<u4_t>(bZero, L::FB_ + s * 16);
+      const float f = __builtin_bit_cast(float, fu[0]);
+      const u2_t m4u = {fu[1], fu[1]}, g4u = {fu[2], fu[2]};  // -(1-f)/c^2 and (1-f), four times each
       const f4_t q4 = lds_ld<f4_t>(bR4, L::QS_ + s * ROWS * 4);
       const float dyj = lds_ld<float>(bC4, L::DYS_ + s * V * 4);
       const h4_t zp = lds_ld<h4_t>(bO, (CMAX + s) * L::STASH_STEP);
@@ -923,43 +925,41 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       for (int c2 = 0; c2 < CT; ++c2)
         hfr[c2] = lds_ld<h4_t>(bH, s * L::STASH_STEP + c2 * 512);
       const h4_t hown = lds_ld<h4_t>(bO, s * L::STASH_STEP);
-      h4_t kfr = lds_ld<h4_t>(bR2, L::KH_ + s * ROWS * 2);
       const bool mine = jlB == s;
-      // H' - Z' and 1 - tanh^2 in packed fp16 (their inputs are fp16 stash values, so fp32
-      // would add nothing); G, the df sum and dS = (1-f) G (1 - tanh^2) in fp32 with the
-      // fp16 factors converted inside the multiply-add
-      const h4_t one4 = {(_Float16)1.f, (_Float16)1.f, (_Float16)1.f, (_Float16)1.f};
+      // k_s in row s of the A operand only: the other lanes read zeros
+      const h4_t kfr = lds_ld<h4_t>(mine ? bR2 + (L::KH_ + s * ROWS * 2) : bZero + L::ZERO_, 0);
+      // H' - Z' and (1-f)(1 - tanh^2) in packed fp16 (their inputs are fp16 stash values, so
+      // fp32 would add nothing); G and the df sum in fp32; dS = G * [(1-f)(1 - tanh^2)] as a
+      // mixed-precision multiply that rounds straight to the fp16 MFMA operand
+      const h4_t m4 = __builtin_bit_cast(h4_t, m4u), g4 = __builtin_bit_cast(h4_t, g4u);
       const h4_t hz = hown - zp;
-      const h4_t uu = (zp * (_Float16)(-kInvC * kInvC)) * zp + one4;
-      h4_t dsp;
+      const h4_t ug = (zp * m4) * zp + g4;
       float dfl = 0.f;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         G[r] = fmaf(q4[r], dyj, carry[r]);
         dfl = fmaf(G[r], (float)hz[r], dfl);
-        dsp[r] = (_Float16)((gm * G[r]) * (float)uu[r]);
       }
+      uint2 dsu;
+      {
+        const uint2 ugu = __builtin_bit_cast(uint2, ug);
+        asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(dsu.x) : "v"(G[0]), "v"(ugu.x));
+        asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]"
+            : "+v"(dsu.x) : "v"(G[1]), "v"(ugu.x));
+        asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel_hi:[0,1,0]" : "=v"(dsu.y) : "v"(G[2]), "v"(ugu.y));
+        asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel:[0,1,0] op_sel_hi:[0,1,0]"
+            : "+v"(dsu.y) : "v"(G[3]), "v"(ugu.y));
+      }
+      const h4_t dsp = __builtin_bit_cast(h4_t, dsu);
 #pragma unroll
       for (int r = 0; r < 4; ++r)
         lds_st<_Float16>(bDw, L::DX + (wr * ROWS + r) * LDH * 2, dsp[r]);
 #pragma unroll
       for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = mfma_k16(hfr[c2], dsp, dWacc[c2]);
-      if (!mine) kfr = h4_t{0, 0, 0, 0};
       dvacc = mfma_k16(kfr, dsp, dvacc);
-      {
-        const uint32_t ub = __builtin_bit_cast(uint32_t, dfl);
-        const float lo = dfl - __builtin_bit_cast(float, ub & 0xFFFF0000u);
-        uint2 av;
-        av.x = (ub >> 16) | (__builtin_bit_cast(uint32_t, lo) & 0xFFFF0000u);
-        av.y = 0u;
-        uint2 bv;
-        bv.x = mine ? 0x3F803F80u : 0u;
-        bv.y = 0u;
-        typedef short s4_t __attribute__((ext_vector_type(4)));
-        dfacc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s4_t, av),
-                                                          __builtin_bit_cast(s4_t, bv), dfacc,
-                                                          0, 0, 0);
-      }
+      // df_s = sum G (H' - Z') / c: fp32 MFMA against ones in column s adds the four lane
+      // groups; the 16 rows of that column are added at the end of the chunk
+      dfacc = __builtin_amdgcn_mfma_f32_16x16x4f32(dfl, mine ? 1.f : 0.f, dfacc, 0, 0, 0);
       fprev = f;
     };
     {
