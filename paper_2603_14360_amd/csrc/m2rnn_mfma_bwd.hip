@@ -513,7 +513,7 @@ template <typename TL>
 struct OvLds {
   static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, LDH2 = TL::LDH2, RB = TL::RB,
                        CT = TL::CT, WAVES = TL::WAVES;
-  static constexpr int HX_BYTES = 2 * ROWS * LDH2 * 2;    // team A exchange, (hi, lo) state
+  static constexpr int HX_BYTES = 2 * ROWS * LDH * 2;     // team A exchange, fp16 state
   static constexpr int DX_BYTES = 2 * ROWS * LDH * 2;     // team B exchange, fp16 dS
   static constexpr int STASH_STEP = RB * CT * 64 * 8;     // one h4 per lane per tile
   static constexpr int VEC_A = ROWS * 4 + V * 4 + V * 4 + 16;          // c*k, v, dy twice (f16), f
@@ -578,7 +578,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   extern __shared__ __attribute__((aligned(16))) char lds[];
   typedef _Float16 XRow2[LDH2];
   typedef _Float16 XRow[LDH];
-  XRow2 *Hx = (XRow2 *)(lds + L::HX);
+  XRow *Hx = (XRow *)(lds + L::HX);
   XRow *Dx = (XRow *)(lds + L::DX);
   auto stH = [&](int buf) { return (h4_t *)(lds + L::ST + (buf * 2 + 0) * CMAX * L::STASH_STEP); };
   auto stZ = [&](int buf) { return (h4_t *)(lds + L::ST + (buf * 2 + 1) * CMAX * L::STASH_STEP); };
@@ -608,16 +608,15 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   if (teamA) {
     // =====================================================================
     // team A: recompute chunk nck-1-it into stash[it & 1], it = 0 .. nck-1
-    h8_t wf[CT];
+    // The recomputed states only feed fp16 stash entries and restart from an fp32 checkpoint
+    // every C steps, so the state enters this team's contraction as a single fp16 value
+    // (the forward kernel needs the (hi, lo) pair because its trajectory runs for all T steps).
+    FragT wf[KS];  // B operand: k-slot e of MFMA ks holds W[32 ks + FE ig + e][col0 + jl]
 #pragma unroll
-    for (int m = 0; m < CT; ++m)
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const _Float16 w =
-            (_Float16)bf16_to_f32(Wn[(size_t)(16 * m + 4 * ig + e) * V + col0 + jl]);
-        wf[m][2 * e] = w;
-        wf[m][2 * e + 1] = w;
-      }
+      for (int e = 0; e < FE; ++e)
+        wf[ks][e] = (_Float16)bf16_to_f32(Wn[(size_t)(32 * ks + FE * ig + e) * V + col0 + jl]);
     bf16_raw rk[NQ], rv[NV], rdy[NV];
     float rf = 1.f;
     float hck[4];
@@ -661,8 +660,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         if (idx < CMAX * V) {
           const float dyf = bf16_to_f32(rdy[m]);
           vS[idx] = bf16_to_f32(rv[m]);
-          dyH[2 * idx] = (_Float16)dyf;
-          dyH[2 * idx + 1] = (_Float16)dyf;
+          dyH[idx] = (_Float16)dyf;
         }
       }
       if (tid < CMAX) {
@@ -671,10 +669,15 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         fA[tid * 4 + 3] = -2.f * (kC * (1.f - rf));
       }
     };
-    auto dq_slice = [&](f4_t acc, const h8_t &af_ct, int s_col, int col) {
-      h8_t bf = *(const h8_t *)&dyH[s_col * 2 * V + 2 * (16 * ct + 4 * ig)];
-      if (jl != col) bf = h8_t{0, 0, 0, 0, 0, 0, 0, 0};
-      return mfma_k32(af_ct, bf, acc);
+    // dq of chunk step s_col (= H after that step, times dy of that step): wave ct < KS adds
+    // its 32-column slice into accumulator column s_col; the other lanes' operand is zero
+    auto dq_slice = [&](f4_t acc, const FragT &af_ct, int s_col) {
+      const FragT bf = *(const FragT *)(jl == s_col ? (const char *)&dyH[s_col * V + FE * ig + 32 * ct]
+                                                    : (const char *)(lds + L::ZERO_));
+      if constexpr (X32)
+        return mfma_k32(af_ct, bf, acc);
+      else
+        return mfma_k16(af_ct, bf, acc);
     };
 
     if (nck > 0) stage_load(nck - 1);
@@ -685,7 +688,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       const int len = active ? ((T - t0) < C ? (T - t0) : C) : 0;
       const int buf = it & 1;
       float h[4];
-      uint32_t pk[4];
+      h4_t hp;  // fp16 copy of the state before the current step (stash entry, MFMA operand)
       int cur = 0;
       f4_t dqacc = zero4;
       if (active) {
@@ -693,11 +696,10 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           h[r] = kC * hck[r];
-          pk[r] = split_hi_lo(h[r]);
+          hp[r] = (_Float16)h[r];
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          *(uint32_t *)&Hx[cur * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+        for (int r = 0; r < 4; ++r) Hx[cur * ROWS + rowb + 4 * ig + r][col0 + jl] = hp[r];
         if (ck > 0) stage_load(ck - 1);  // next chunk's vectors travel during this chunk
       }
       lds_barrier();  // P
@@ -705,18 +707,23 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       // in the unrolled loop below (per-step loop overhead costs as much as the arithmetic)
       auto stepA = [&](int s) __attribute__((always_inline)) {
         const int rd = s & 1, wr = rd ^ 1;
-        h8_t af[CT];
+        FragT af[KS];
 #pragma unroll
-        for (int m = 0; m < CT; ++m)
-          af[m] = *(const h8_t *)&Hx[rd * ROWS + rowb + jl][2 * (16 * m + 4 * ig)];
+        for (int ks = 0; ks < KS; ++ks)
+          af[ks] = *(const FragT *)&Hx[rd * ROWS + rowb + jl][FE * ig + 32 * ks];
         const float f = fA[s * 4 + 0], gp = fA[s * 4 + 1], m2g = fA[s * 4 + 3];
         const f4_t k4 = *(const f4_t *)&kS[s * ROWS + rowb + 4 * ig];
         const float vj = vS[s * V + col0 + jl];
         f4_t acc = zero4;
 #pragma unroll
-        for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
+        for (int ks = 0; ks < KS; ++ks) {
+          if constexpr (X32)
+            acc = mfma_k32(af[ks], wf[ks], acc);
+          else
+            acc = mfma_k16(af[ks], wf[ks], acc);
+        }
         settle(acc);
-        stH(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = hi_of_pairs(pk);
+        stH(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = hp;
         h4_t zp;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -727,16 +734,15 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
           const float z = fmaf(-2.f * kC, rr, kC);
           h[r] = fmaf(m2g, rr, t1);
           zp[r] = (_Float16)z;
-          pk[r] = split_hi_lo(h[r]);
+          hp[r] = (_Float16)h[r];
         }
         stZ(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = zp;
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          *(uint32_t *)&Hx[wr * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
-        if (s > 0) {  // dq slice of the previous step; af still holds the state after it
+        for (int r = 0; r < 4; ++r) Hx[wr * ROWS + rowb + 4 * ig + r][col0 + jl] = hp[r];
+        if (s > 0 && ct < KS) {  // dq slice of the previous step; af still holds the state after it
 #pragma unroll
-          for (int m = 0; m < CT; ++m)
-            if (ct == m) dqacc = dq_slice(dqacc, af[m], s - 1, s - 1);
+          for (int ks = 0; ks < KS; ++ks)
+            if (ct == ks) dqacc = dq_slice(dqacc, af[ks], s - 1);
         }
       };
       if (C == CMAX) {
@@ -753,9 +759,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         }
       }
       cur = len & 1;
-      if (active) {  // dq of the chunk's last step, from the state after it
-        const h8_t afl = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * ct + 4 * ig)];
-        dqacc = dq_slice(dqacc, afl, len - 1, len - 1);
+      if (active && ct < KS) {  // dq of the chunk's last step, from the state after it
+        const FragT afl = *(const FragT *)&Hx[cur * ROWS + rowb + jl][FE * ig + 32 * ct];
+        dqacc = dq_slice(dqacc, afl, len - 1);
       }
       lds_barrier();  // E1: exchange buffer free, it carries the dq partials now
       f4_t *fin = (f4_t *)(lds + L::HX);
@@ -764,7 +770,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       if (active && ct == 0 && jl < len) {
         f4_t d = fin[(rb * CT + 0) * 64 + lane];
 #pragma unroll
-        for (int c2 = 1; c2 < CT; ++c2) d += fin[(rb * CT + c2) * 64 + lane];
+        for (int ks = 1; ks < KS; ++ks) d += fin[(rb * CT + ks) * 64 + lane];
         d *= kInvC;
         const int t = t0 + jl;
         if (ws.dqh)
