@@ -41,6 +41,9 @@ def lib():
             raise RuntimeError(
                 "libm2rnn.so is not built (%s); run `python -m paper_2603_14360_amd.build`. "
                 "There is no fallback path." % LIB_PATH)
+        # torch first: it ships its own HIP runtime, and the library must bind to that copy
+        # (the one that owns the tensors and streams passed in), not load a second one
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, sz, dp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(m2rnn_desc)
         L.m2rnn_status_string.restype = ctypes.c_char_p

@@ -46,10 +46,6 @@ size_t mfma_workspace_bytes(int B, int T, int N, int Nqk, int K, int V, int C, i
 hipError_t mfma_fwd(const FwdArgs &a, hipStream_t s);
 hipError_t mfma_bwd(const BwdArgs &a, hipStream_t s);
 
-// two row blocks per wave, software pipelined (same workspace and outputs as mfma_fwd with RB = 2)
-bool pair_fwd_supported(int K, int V);
-hipError_t pair_fwd(const FwdArgs &a, hipStream_t s);
-
 // ---- register-resident path (bf16 io, V <= 64): one wave per 16 state rows ----
 bool rowwave_supported(int K, int V);
 hipError_t rowwave_fwd(const FwdArgs &a, hipStream_t s);

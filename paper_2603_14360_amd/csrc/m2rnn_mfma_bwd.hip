@@ -576,7 +576,6 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   const int row_base = part * ROWS;
 
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  typedef _Float16 XRow2[LDH2];
   typedef _Float16 XRow[LDH];
   XRow *Hx = (XRow *)(lds + L::HX);
   XRow *Dx = (XRow *)(lds + L::DX);

@@ -115,7 +115,6 @@ struct Tile {
   static constexpr int KS = X32 ? V / 32 : 1;  // MFMAs per state contraction
   static constexpr int LDH = V + 8;            // halfs per row of a row-major fp16 exchange buffer
   static constexpr int LDH2 = 2 * V + 8;       // ... of a (hi, lo) pair exchange buffer
-  static constexpr int GROUPS = 1;             // >1: row-block groups run half a step apart (measured: no gain)
   static_assert(K % (16 * RB) == 0 && V % 16 == 0 && WAVES <= 16, "bad tile");
 };
 

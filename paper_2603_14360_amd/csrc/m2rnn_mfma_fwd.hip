@@ -35,13 +35,12 @@ struct FwdSmem {
   alignas(16) _Float16 qS[2][TB][TL::ROWS];
   alignas(16) float vS[2][TB][TL::V];
   alignas(16) float fS[2][TB][4];                  // f, c(1-f), -2c(1-f), unused
-  alignas(16) f4_t yB[TL::RB][2][TL::CT][64];      // readout accumulators of a block (by block parity)
+  alignas(16) f4_t yB[TL::RB][TL::CT][64];         // readout accumulators of one block
 };
 
-template <typename TL, bool PP, bool DO_Y>
+template <typename TL, bool DO_Y>
 __global__ void __launch_bounds__(TL::THREADS)
     mfma_fwd_kernel(FwdArgs a, float *__restrict__ ypart_ws) {
-  static_assert(!PP || TL::RB == 2, "ping-pong needs two row blocks");
   constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS;
   constexpr int THREADS = TL::THREADS;
   constexpr int NQ = (TB * ROWS + THREADS - 1) / THREADS;
@@ -243,62 +242,11 @@ __global__ void __launch_bounds__(TL::THREADS)
     }
   };
 
-  if constexpr (PP) {
-    // ---- ping-pong schedule.  Row block 0 (waves 0..CT-1) and row block 1 run half a step
-    // apart, two barriers per step: between two barriers one row block reads its operand
-    // and runs the contraction (LDS latency, matrix core) while the other does the
-    // elementwise update and the write-back (vector ALU).  Waves w and w + CT share a
-    // SIMD, so the SIMD's vector ALU serves one of them at a time.
-    auto flush = [&](int fb) {  // row block 0's waves: add the two row blocks' y, store
-      const int ft0 = fb * TB;
-      const int flen = (T - ft0) < TB ? (T - ft0) : TB;
-      y_store(sm.yB[0][fb & 1][ct][lane] + sm.yB[1][fb & 1][ct][lane], ft0, flen);
-    };
-    int flushed = 0;             // y blocks stored so far (row block 0's waves only)
-    if (rb == 1) lds_barrier();  // row block 1 starts half a step late
-    for (int blk = 0; blk < nblk; ++blk) {
-      const int t0 = blk * TB;
-      const int len = (T - t0) < TB ? (T - t0) : TB;
-      const int sb = blk & 1;
-      const bool more = blk + 1 < nblk;
-      if (more) stage_load(t0 + TB);
-      f4_t yacc = {0.f, 0.f, 0.f, 0.f};
-      auto step = [&](int s) __attribute__((always_inline)) {
-        StepRegs x;
-        ckpt_store(t0 + s);
-        step_R(x, s, sb, 0);
-        if (s == TB / 2 && more) stage_store(sb ^ 1);
-        if (DO_Y && s == 1 && rb == 0 && flushed < blk) {  // the other row block's part of
-          flush(blk - 1);                                  // block blk-1 is visible by now
-          flushed = blk;
-        }
-        lds_barrier();
-        uint32_t pk[4];
-        step_E(x, pk, 0);
-        if constexpr (DO_Y) {
-          step_Y(x, pk, s, yacc);
-          if (s == len - 1) {
-            settle(yacc);
-            sm.yB[rb][sb][ct][lane] = yacc;
-          }
-        }
-        lds_barrier();
-      };
-      if (len == TB) {
-#pragma unroll
-        for (int s = 0; s < TB; ++s) step(s);
-      } else {
-#pragma nounroll
-        for (int s = 0; s < len; ++s) step(s);
-      }
-    }
-    if (rb == 0) {
-      lds_barrier();  // pairs with row block 1's last barrier: its last y block is visible
-      if constexpr (DO_Y)
-        for (int fb = flushed; fb < nblk; ++fb) flush(fb);
-    }
-  } else {
-    // ---- lock-step schedule: one barrier per step, exchange buffer alternates
+  {
+    // ---- lock-step schedule: one barrier per step, exchange buffer alternates.
+    // (A ping-pong schedule -- the two row blocks of a workgroup half a step apart, two
+    //  barriers per step, so that the waves sharing a SIMD alternate between operand fetch
+    //  and vector-ALU work -- was measured 10 % slower at B*N = 128, K = V = 64.)
     for (int blk = 0; blk < nblk; ++blk) {
       const int t0 = blk * TB;
       const int len = (T - t0) < TB ? (T - t0) : TB;
@@ -327,11 +275,11 @@ __global__ void __launch_bounds__(TL::THREADS)
       if constexpr (DO_Y) {
         // ---- block flush: sum the row blocks, store the block's rows of y
         if constexpr (RB > 1) {
-          if (rb > 0) sm.yB[rb][0][ct][lane] = yacc;
+          if (rb > 0) sm.yB[rb][ct][lane] = yacc;
           lds_barrier();
           if (rb == 0) {
 #pragma unroll
-            for (int r2 = 1; r2 < RB; ++r2) yacc += sm.yB[r2][0][ct][lane];
+            for (int r2 = 1; r2 < RB; ++r2) yacc += sm.yB[r2][ct][lane];
           }
           // (yB is written again only 16 steps, i.e. at least 16 barriers, later)
         }
@@ -363,12 +311,11 @@ hipError_t launch_fwd(const FwdArgs &a, hipStream_t s) {
   const int units = a.B * a.N;
   if (units == 0) return hipSuccess;
   float *ypart = (float *)a.ws;
-  constexpr bool PP = false;  // (TL::RB == 2 would run the ping-pong schedule: measured slower)
   if (a.write_y)
-    hipLaunchKernelGGL((mfma_fwd_kernel<TL, PP, true>), dim3(grid_blocks(units, TL::P)),
+    hipLaunchKernelGGL((mfma_fwd_kernel<TL, true>), dim3(grid_blocks(units, TL::P)),
                        dim3(TL::THREADS), 0, s, a, ypart);
   else
-    hipLaunchKernelGGL((mfma_fwd_kernel<TL, PP, false>), dim3(grid_blocks(units, TL::P)),
+    hipLaunchKernelGGL((mfma_fwd_kernel<TL, false>), dim3(grid_blocks(units, TL::P)),
                        dim3(TL::THREADS), 0, s, a, ypart);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
