@@ -101,7 +101,7 @@ def main():
     dev["f"] = torch.from_numpy(inp["f"]).to("cuda")
     for n in ("H0", "dHT"):
         dev[n] = None if inp[n] is None else torch.from_numpy(inp[n]).to("cuda")
-    scan = mb.Scan(wl.B, wl.T, wl.N, wl.K, wl.V, wl.io, backward=wl.backward)
+    scan = mb.Scan(wl.B, wl.T, wl.N, wl.K, wl.V, wl.io, Nqk=(wl.Nqk or None), backward=wl.backward)
 
     def step():
         scan.fwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"])
@@ -152,8 +152,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 state, f16 matrix-core operands, bf16 io" if wl.io == "bf16" else "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: B=%d N=%d K=%d V=%d T=%d %s io, fwd%s" % (
-            wl.name, wl.B, wl.N, wl.K, wl.V, wl.T, wl.io, "+bwd" if wl.backward else ""),
+        "config": {"workload": "%s: B=%d N=%d%s K=%d V=%d T=%d %s io, fwd%s" % (
+            wl.name, wl.B, wl.N, " (Nqk=%d)" % wl.Nqk if wl.Nqk else "", wl.K, wl.V, wl.T, wl.io,
+            "+bwd" if wl.backward else ""),
             "tokens_per_step": tokens, "chunk": mb.m2rnn_default_chunk(scan.desc)},
         "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
         "roofline": {

@@ -520,7 +520,7 @@ struct OvLds {
   static constexpr int VEC_B = ROWS * 4 + V * 4 + ROWS * 2 + V * 2 + 16;  // q, dy, k f16, v f16, f
   static constexpr int PER_STEP = 4 * STASH_STEP + VEC_A + VEC_B;
   static constexpr int FIXED = HX_BYTES + DX_BYTES;
-  static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 352) / PER_STEP;
+  static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 448) / PER_STEP;
   static constexpr int CMAX = CMAX_RAW > 8 ? 8 : CMAX_RAW;  // two chunks share 16 accumulator columns
   // usable: both teams fit the workgroup and the register file, the stash holds a few steps,
   // and team B's stash half can hold its end-of-chunk partials
@@ -542,7 +542,8 @@ struct OvLds {
   static constexpr int VH_ = KH_ + C_ * ROWS * 2;          //         half v    [C][V]
   static constexpr int FB_ = VH_ + C_ * V * 2;             //         f; f16x2 -(1-f)/c^2; f16x2 (1-f); -
   static constexpr int ZERO_ = FB_ + C_ * 16;              // 32 zero bytes (masked operand reads)
-  static constexpr int ST = (ZERO_ + 32 + 255) & ~255;     // [2][ {H, Z} ][C][RB][CT][64] h4
+  static constexpr int SCL_ = ZERO_ + 32;                  // team B: per-wave maxima [3][8] floats
+  static constexpr int ST = (SCL_ + 96 + 255) & ~255;      // [2][ {H, Z} ][C][RB][CT][64] h4
   static constexpr int BYTES = ST + 4 * C_ * STASH_STEP;
   static_assert(!OK || BYTES <= kLdsLimit, "LDS overflow");
 };
@@ -602,7 +603,8 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   const size_t st_off = (size_t)unit * K * V + tile_off;
   const int nck = (T + C - 1) / C;
   const f4_t zero4 = {0.f, 0.f, 0.f, 0.f};
-  if (threadIdx.x < 8) ((uint32_t *)(lds + L::ZERO_))[threadIdx.x] = 0u;  // visible after barrier P
+  if (threadIdx.x < 32) ((uint32_t *)(lds + L::ZERO_))[threadIdx.x] = 0u;  // zero pad and the
+                                                                          // maxima slots behind it; visible after barrier P
 
   if (teamA) {
     // =====================================================================
@@ -656,10 +658,16 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
 #pragma unroll
       for (int m = 0; m < NV; ++m) {
         const int idx = tid + m * THREADS;
-        if (idx < CMAX * V) {
-          const float dyf = bf16_to_f32(rdy[m]);
+        // dy_s enters the dq contraction as fp16: each step's row is scaled by a power of two
+        // so that its largest entry lands in [2^10, 2^11) (loss-scaled or token-averaged
+        // gradients are far outside the fp16 range); column s of dq is scaled back at the end
+        const bool in = idx < CMAX * V;
+        const float dyf = in ? bf16_to_f32(rdy[m]) : 0.f;
+        const int e = ilog2f(fminf(fmaxf(group_max_nonneg<V>(fabsf(dyf)), 1e-30f), 1e30f));
+        if (in) {
           vS[idx] = bf16_to_f32(rv[m]);
-          dyH[idx] = (_Float16)dyf;
+          dyH[idx] = (_Float16)(dyf * pow2i(10 - e));
+          if (idx % V == 0) fA[(idx / V) * 4 + 2] = pow2i(e - 10);
         }
       }
       if (tid < CMAX) {
@@ -770,7 +778,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         f4_t d = fin[(rb * CT + 0) * 64 + lane];
 #pragma unroll
         for (int ks = 1; ks < KS; ++ks) d += fin[(rb * CT + ks) * 64 + lane];
-        d *= kInvC;
+        d *= kInvC * fA[jl * 4 + 2];  // undo this step's dy scale
         const int t = t0 + jl;
         if (ws.dqh)
           *(f4_t *)&ws.dqh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
@@ -797,6 +805,16 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   f4_t dWacc[CT];
 #pragma unroll
   for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = zero4;
+  // Dynamic range of the fp16 dS operand.  The carried gradient of this recurrence can grow
+  // (or shrink) by orders of magnitude over a long sequence; dS would leave the fp16 range.
+  // The sweep therefore works on sc * (carry, G, dS, and every accumulator fed by dS) with
+  // sc a power of two chosen per chunk from the largest |carry| in the workgroup and the
+  // largest |q| |dy| of the chunk, so that the scaled magnitudes start the chunk in
+  // [2^8, 2^9): a factor 2^7 of growth inside the chunk still fits, small values keep
+  // their mantissa.  Powers of two make the scaling exact; outputs are divided by sc.
+  float sc = 1.f, isc = 1.f;
+  float *scl = (float *)(lds + L::SCL_);
+  auto wave_max = [&](float x) { return group_max_nonneg<64>(x); };
 
   bf16_raw rq[NQ], rk[NQ], rv[NV], rdy[NV];
   float rf = 1.f;
@@ -843,6 +861,19 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         vH[idx] = (_Float16)bf16_to_f32(rv[m]);
       }
     }
+    {
+      float mq = 0.f, md = 0.f;
+#pragma unroll
+      for (int m = 0; m < NQ; ++m) mq = fmaxf(mq, fabsf(bf16_to_f32(rq[m])));
+#pragma unroll
+      for (int m = 0; m < NV; ++m) md = fmaxf(md, fabsf(bf16_to_f32(rdy[m])));
+      mq = wave_max(mq);
+      md = wave_max(md);
+      if (lane == 0) {
+        scl[8 + wave] = mq;
+        scl[16 + wave] = md;
+      }
+    }
     if (tid < CMAX) {
       const float gm = 1.f - rf;
       const h2_t m2 = {(_Float16)(gm * (-kInvC * kInvC)), (_Float16)(gm * (-kInvC * kInvC))};
@@ -865,6 +896,26 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       if (ck > 0) stage_load(ck - 1);
     }
     lds_barrier();  // P: stash[buf] was completed by team A in the previous iteration
+    if (active) {  // scale of this chunk (wave-uniform, identical in every wave of the team)
+      float mc = 0.f, mq = 0.f, md = 0.f;
+#pragma unroll
+      for (int w4 = 0; w4 < (WAVES + 3) / 4; ++w4) {  // slots of absent waves hold zero
+        const f4_t xc = *(const f4_t *)&scl[4 * w4], xq = *(const f4_t *)&scl[8 + 4 * w4],
+                   xd = *(const f4_t *)&scl[16 + 4 * w4];
+        mc = fmaxf(mc, fmaxf(fmaxf(xc[0], xc[1]), fmaxf(xc[2], xc[3])));
+        mq = fmaxf(mq, fmaxf(fmaxf(xq[0], xq[1]), fmaxf(xq[2], xq[3])));
+        md = fmaxf(md, fmaxf(fmaxf(xd[0], xd[1]), fmaxf(xd[2], xd[3])));
+      }
+      const int e = ilog2f(fminf(fmaxf(mc + mq * md, 1e-30f), 1e30f));
+      const float sc_new = pow2i(8 - e);
+      const float ratio = sc_new * isc;  // exact: both are powers of two
+      sc = sc_new;
+      isc = pow2i(e - 8);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) carry[r] *= ratio;
+#pragma unroll
+      for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] *= ratio;
+    }
     f4_t dkacc = zero4, dvacc = zero4, dfacc = zero4;
     float G[4] = {0.f, 0.f, 0.f, 0.f};
     float fprev = 0.f;
@@ -923,7 +974,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       const float f = __builtin_bit_cast(float, fu[0]);
       const u2_t m4u = {fu[1], fu[1]}, g4u = {fu[2], fu[2]};  // -(1-f)/c^2 and (1-f), four times each
       const f4_t q4 = lds_ld<f4_t>(bR4, L::QS_ + s * ROWS * 4);
-      const float dyj = lds_ld<float>(bC4, L::DYS_ + s * V * 4);
+      const float dyj = sc * lds_ld<float>(bC4, L::DYS_ + s * V * 4);
       const h4_t zp = lds_ld<h4_t>(bO, (CMAX + s) * L::STASH_STEP);
       h4_t hfr[CT];
 #pragma unroll
@@ -985,17 +1036,22 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       // R2 of the chunk's first step; a short chunk already ran it at super-step u == len
       if (active && len == C) R2(sprev, cur ^ 1);
     }
+    {  // largest true |carry| of this wave, for the next chunk's scale
+      float mc = fmaxf(fmaxf(fabsf(carry[0]), fabsf(carry[1])), fmaxf(fabsf(carry[2]), fabsf(carry[3])));
+      mc = wave_max(mc) * isc;
+      if (lane == 0) scl[wave] = mc;
+    }
     lds_barrier();  // E1: all reads of this chunk's stash half are done: it takes the partials
     f4_t *fin = (f4_t *)(lds + L::ST + (buf * 2) * CMAX * L::STASH_STEP);
     if (active) {
-      fin[wave * 64 + lane] = dkacc;
-      fin[(WAVES + wave) * 64 + lane] = dvacc;
+      fin[wave * 64 + lane] = dkacc * isc;
+      fin[(WAVES + wave) * 64 + lane] = dvacc * isc;
       float x = (dfacc[0] + dfacc[1]) + (dfacc[2] + dfacc[3]);
       x += __shfl_xor(x, 16, 64);
       x += __shfl_xor(x, 32, 64);
       if (lane < 16 && jl < len)
         ws.dfp[((size_t)(part * WAVES + wave) * a.B * T + (size_t)b * T + t0 + jl) * N + n] =
-            x * kInvC;
+            x * (kInvC * isc);
     }
     lds_barrier();  // E2
     if (active) {
@@ -1032,14 +1088,14 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
 
   if (a.dH0)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) a.dH0[st_off + (size_t)r * V] = carry[r];
+    for (int r = 0; r < 4; ++r) a.dH0[st_off + (size_t)r * V] = carry[r] * isc;
   {
     float *dst = ws.dWp + (((size_t)unit * TL::P + part) * RB + rb) * V * V;
 #pragma unroll
     for (int c2 = 0; c2 < CT; ++c2)
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        dst[(size_t)(c2 * 16 + 4 * ig + r) * V + col0 + jl] = dWacc[c2][r] * kInvC;
+        dst[(size_t)(c2 * 16 + 4 * ig + r) * V + col0 + jl] = dWacc[c2][r] * (kInvC * isc);
   }
 }
 

@@ -103,6 +103,38 @@ __device__ __forceinline__ f4_t mfma_k16(h4_t a, h4_t b, f4_t c) {
 // that skip the block read the accumulator too early (seen as wrong gradients).
 __device__ __forceinline__ void settle(f4_t &d) { asm volatile("" : "+v"(d)); }
 
+// Maximum of a NON-NEGATIVE float over aligned groups of G = 16, 32 or 64 consecutive lanes
+// (result in every lane of the group), without LDS traffic: four DPP steps inside each row
+// of 16 lanes, then the rows through scalar registers.  Non-negative floats order like
+// their bit patterns, so the maxima are taken on integers.
+template <int G>
+__device__ __forceinline__ float group_max_nonneg(float x) {
+  static_assert(G == 16 || G == 32 || G == 64, "group size");
+  int v = __builtin_bit_cast(int, x);
+  v = max(v, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, false));  // row_mirror
+  if constexpr (G > 16) {
+    const int r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+    const int r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+    if constexpr (G == 64)
+      v = max(max(r0, r1), max(r2, r3));
+    else
+      v = (threadIdx.x & 32) ? max(r2, r3) : max(r0, r1);
+  }
+  return __builtin_bit_cast(float, v);
+}
+// 2^e with e clamped to the normal range
+__device__ __forceinline__ float pow2i(int e) {
+  e = e < -126 ? -126 : (e > 127 ? 127 : e);
+  return __builtin_bit_cast(float, (uint32_t)(127 + e) << 23);
+}
+// floor(log2 x) of a positive finite float (subnormals count as 2^-127)
+__device__ __forceinline__ int ilog2f(float x) {
+  return (int)((__builtin_bit_cast(uint32_t, x) >> 23) & 255u) - 127;
+}
+
 template <int K_, int V_, int RB_>
 struct Tile {
   static constexpr int K = K_, V = V_, RB = RB_;
@@ -138,8 +170,7 @@ inline int grid_blocks(int units, int P) { return 8 * P * ((units + 7) / 8); }
 
 // (K, V, RB) tilings that are instantiated
 #define M2RNN_TILE_CASES(X)                                                                      \
-  X(64, 64, 2) X(64, 64, 1) X(128, 128, 1) X(32, 32, 2) X(32, 32, 1) X(16, 16, 1) X(64, 16, 4)   \
-  X(64, 16, 1)
+  X(64, 64, 2) X(64, 64, 1) X(128, 128, 1) X(32, 32, 2) X(32, 32, 1) X(16, 16, 1) X(64, 16, 1)
 
 // (K, V) shapes of the register-resident (one wave per row block) kernels
 #define M2RNN_ROWWAVE_CASES(X)                                                                  \

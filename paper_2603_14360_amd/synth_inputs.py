@@ -5,7 +5,7 @@ tensors, scales them, and rounds them to the storage type.  Both the float64
 oracle and the GPU library are fed from here, so that they see bit-identical
 values (the oracle receives the already-rounded values widened to float64).
 
-The five named workloads stand in for the paper's language-model activations
+The named workloads stand in for the paper's language-model activations
 (training context 4096, K = 64, bf16 storage), which are not available here.
 
 Recipe: one ``numpy.random.default_rng(seed)`` stream, standard-normal float64
@@ -47,6 +47,9 @@ WORKLOADS = {
     "C4": Workload("C4", 4, 8192, 8, 128, 128, "bf16", 3, 128 ** -0.5, 2.0),
     "C5": Workload("C5", 1, 65536, 32, 64, 64, "bf16", 4, 0.125, 3.0,
                    backward=False),
+    # the paper's own layer shape (state-size appendix: K = 64, V = 16; 84 heads at the 410M
+    # scale; q and k shared by all heads, i.e. the multi-value form of Algorithms 1 and 2)
+    "P1": Workload("P1", 8, 4096, 84, 64, 16, "bf16", 5, 0.125, 2.0, Nqk=1),
 }
 
 
@@ -118,12 +121,21 @@ def make_inputs(wl, T=None, B=None, N=None):
 
 
 def select_heads(inp, heads):
-    """Restrict per-head workload tensors (Nqk = N) to a list of heads; the
-    recurrences of different heads are independent, so the oracle can be run
-    on the selection alone."""
+    """Restrict workload tensors to a list of heads; the recurrences of
+    different heads are independent, so the oracle can be run on the selection
+    alone.  With one q/k head per head (Nqk = N) q and k are restricted too;
+    with shared q/k (Nqk = 1) they are kept whole, and dq, dk of the selection
+    are then sums over the selected heads only."""
     heads = list(heads)
     out = {}
-    for name in ("q", "k", "v", "dy"):
+    per_head_qk = inp["q"].shape[2] == inp["v"].shape[2]
+    for name in ("q", "k"):
+        if per_head_qk:
+            out[name] = np.ascontiguousarray(inp[name][:, :, heads])
+        else:
+            assert inp[name].shape[2] == 1, "select_heads: Nqk must be N or 1"
+            out[name] = inp[name]
+    for name in ("v", "dy"):
         out[name] = np.ascontiguousarray(inp[name][:, :, heads])
     out["f"] = np.ascontiguousarray(inp["f"][:, :, heads])
     out["W"] = np.ascontiguousarray(inp["W"][heads])

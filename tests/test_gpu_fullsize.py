@@ -15,6 +15,8 @@ pytestmark = pytest.mark.gpu
 def _slice_heads(out, heads):
     res = {}
     for n, x in out.items():
+        if n in ("dq", "dk") and x.shape[2] == 1:
+            continue  # shared q/k heads: sums over all heads, not a per-head output
         if n in ("y", "dq", "dk", "dv"):
             res[n] = x[:, :, heads]
         elif n == "df":
@@ -64,3 +66,32 @@ def test_prefix_backward_C4_shape():
     ref = gu.run_oracle(select_heads(inp, [1, 6]))
     errs = gu.compare(got, ref, gu.TOL[wl.io], label="C4 prefix")
     print("C4 T=1024", {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)
+
+
+def test_production_shape_shared_qk():
+    """The paper's layer shape (K = 64, V = 16, 84 heads, q/k shared by all heads) at full
+    size: per-head outputs (y, dv, df, dW, H_T, dH0) of sampled heads against the oracle.
+    dq and dk are sums over all 84 heads and are covered by the next test."""
+    wl = WORKLOADS["P1"]
+    heads = [0, 41, 83]
+    print("case P1 generating", flush=True)
+    inp = make_inputs(wl)
+    print("case P1 gpu", flush=True)
+    got = _slice_heads(gu.run_gpu(inp, wl.io), heads)
+    print("case P1 oracle on heads", heads, flush=True)
+    ref = gu.run_oracle(select_heads(inp, heads))
+    names = ("y", "HT", "dv", "df", "dW", "dH0")
+    errs = gu.compare(got, ref, gu.TOL[wl.io], names=names, label="P1")
+    print("P1", {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)
+
+
+def test_production_shape_all_heads_prefix():
+    """Same shape, all 84 heads, T = 512: every output including the head-summed dq, dk."""
+    wl = WORKLOADS["P1"]
+    inp = make_inputs(wl, T=512)
+    print("case P1 T=512 gpu", flush=True)
+    got = gu.run_gpu(inp, wl.io)
+    print("case P1 T=512 oracle", flush=True)
+    ref = gu.run_oracle(inp)
+    errs = gu.compare(got, ref, gu.TOL[wl.io], label="P1 T=512")
+    print("P1 T=512", {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)

@@ -168,3 +168,20 @@ def test_saturated_tanh_bf16():
     got = gu.run_gpu(inp, "bf16")
     ref = gu.run_oracle(inp)
     gu.compare(got, ref, gu.TOL["bf16"], label="saturated")
+
+
+@pytest.mark.parametrize("K,V", [(64, 64), (32, 32), (64, 16), (16, 16)])
+@pytest.mark.parametrize("scale", [2.0 ** -24, 2.0 ** 18])
+def test_gradient_dynamic_range_bf16(K, V, scale):
+    """dy and dH_T far outside the fp16 range (token-averaged losses give ~1e-7, loss scaling
+    gives ~1e5): the backward is linear in (dy, dH_T), so every gradient must scale with
+    them and keep its accuracy; nothing may overflow or flush to zero on the way."""
+    wl = _small("bf16", 2, 70, 2, K, V, seed=77 + K + V)
+    inp = make_inputs(wl)
+    inp["dy"] = (inp["dy"] * np.float32(scale)).astype(np.float32)    # exact: power of two
+    inp["dHT"] = (inp["dHT"] * np.float32(scale)).astype(np.float32)
+    label = "range K%d V%d x%g" % (K, V, scale)
+    print("case", label, flush=True)
+    got = gu.run_gpu(inp, "bf16")
+    ref = gu.run_oracle(inp)
+    _report(label, gu.compare(got, ref, gu.TOL["bf16"], label=label))
