@@ -2,15 +2,19 @@
 // state gradient added to q dy^T and propagated as  f G + dS W^T.
 //
 // The paper's kernel stores every H_t to HBM in a first pass and reloads it in
-// the reverse sweep.  Here the forward leaves one fp32 checkpoint every C steps;
-// the backward walks the chunks from last to first and, per chunk,
-//   phase A  recomputes the chunk forward from its checkpoint (same arithmetic
-//            as the forward kernel), parking for every step the fp16 state
-//            before the step (hi of H'_{t-1} = c H_{t-1}) and Z'_t = c tanh(.)
-//            in an on-chip stash (LDS);
-//   phase B  sweeps the chunk in reverse, reading the stash: no tanh and no
-//            state contraction are recomputed there.
-// Per step of phase B and wavefront (16 x 16 tile, lane = 4 rows x 1 column):
+// the reverse sweep.  Here the forward leaves one fp32 checkpoint every C steps
+// and the backward recomputes each chunk into an on-chip stash (LDS).  A
+// workgroup holds two teams of wavefronts that run at the same time:
+//   team A  recomputes chunk c-1 forward from its checkpoint, parking for every
+//           step the fp16 state before the step (H'_{t-1} = c H_{t-1}) and
+//           Z'_t = c tanh(.) in one half of the double-buffered stash, and
+//           accumulates dq_t = H_t dy_t;
+//   team B  sweeps chunk c in reverse out of the other half: no tanh and no
+//           state contraction are recomputed there.
+// Recomputing a chunk needs only its checkpoint, so it does not wait for the
+// sweep of the chunk after it.  Both teams meet at one workgroup barrier per
+// step, which each needs anyway for its own LDS exchange.
+// Per step of team B and wavefront (16 x 16 tile, lane = 4 rows x 1 column):
 //   G  = q_i dy_j + Ccarry                       (dL/dH_t)
 //   dS = (1-f) G (1 - Z^2)                       -> fp16, to LDS (row-major)
 //   dW' += H'_{t-1}^T dS       MFMA k = rows     (A = stash tiles, B = own dS)
@@ -19,8 +23,8 @@
 // scalar df_t = sum G (H_{t-1} - Z_t) never leave the matrix core during a
 // chunk: each is one more MFMA whose second operand (dy_t, v_t, k_t, ones) is
 // placed in column / row (t mod chunk) only, so a 16 x 16 accumulator collects
-// the chunk's 16 steps side by side and nothing is read back per step.  At the
-// end of a phase the partial accumulators of the waves are added through LDS
+// the chunk's steps side by side and nothing is read back per step.  At the
+// end of a chunk the partial accumulators of the waves are added through LDS
 // in a fixed order and stored; nothing uses atomics.
 #include "m2rnn_kernels.hpp"
 #include "m2rnn_mfma_common.hpp"
@@ -29,35 +33,6 @@ namespace m2rnn {
 namespace {
 
 constexpr int kChunkCap = 16;  // = MFMA N: one accumulator column per step of a chunk
-
-template <typename TL>
-struct BwdLds {
-  static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, LDH2 = TL::LDH2, RB = TL::RB,
-                       CT = TL::CT, WAVES = TL::WAVES;
-  static constexpr int X_BYTES = 2 * ROWS * LDH2 * 2;     // exchange: (hi, lo) state in phase A,
-                                                          // fp16 dS in phase B, partials at the ends
-  static constexpr int STASH_STEP = RB * CT * 64 * 8;     // one h4 per lane per tile
-  static constexpr int VEC_STEP = ROWS * (4 + 4 + 2) + V * (4 + 4 + 2 + 4) + 16;
-  static constexpr int PER_STEP = 2 * STASH_STEP + VEC_STEP;
-  static constexpr int CMAX_RAW = (kLdsLimit - X_BYTES - 64) / PER_STEP;
-  static constexpr int CMAX = CMAX_RAW > kChunkCap ? kChunkCap : CMAX_RAW;
-  static_assert(CMAX >= 1, "no room for a stash");
-  static_assert(X_BYTES >= 2 * WAVES * 64 * 16, "exchange buffer too small for the partials");
-  // byte offsets for a stash of CMAX steps
-  static constexpr int X = 0;
-  static constexpr int SH = X + X_BYTES;
-  static constexpr int SZ = SH + CMAX * STASH_STEP;
-  static constexpr int KS_ = SZ + CMAX * STASH_STEP;      // float c*k   [C][ROWS]
-  static constexpr int QS_ = KS_ + CMAX * ROWS * 4;       // float q     [C][ROWS]
-  static constexpr int VS_ = QS_ + CMAX * ROWS * 4;       // float v     [C][V]
-  static constexpr int DYS_ = VS_ + CMAX * V * 4;         // float dy    [C][V]
-  static constexpr int KH_ = DYS_ + CMAX * V * 4;         // half k      [C][ROWS]
-  static constexpr int VH_ = KH_ + CMAX * ROWS * 2;       // half v      [C][V]
-  static constexpr int DYH_ = VH_ + CMAX * V * 2;         // half dy, each value twice [C][2V]
-  static constexpr int FS_ = DYH_ + CMAX * V * 4;         // float f, c(1-f), 1-f, -2c(1-f) [C][4]
-  static constexpr int BYTES = FS_ + CMAX * 16;
-  static_assert(BYTES <= kLdsLimit, "LDS overflow");
-};
 
 struct BwdWs {
   float *dvp;   // [P][B,T,N,V]      (P > 1)
@@ -74,441 +49,8 @@ __device__ __forceinline__ uint2 pack4_bf16(f4_t x) {
   return p;
 }
 
-template <typename TL>
-__global__ void __launch_bounds__(TL::THREADS) mfma_bwd_kernel(BwdArgs a, BwdWs ws) {
-  constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS, KS = TL::KS,
-                LDH = TL::LDH, LDH2 = TL::LDH2, WAVES = TL::WAVES;
-  constexpr int THREADS = TL::THREADS;
-  constexpr bool X32 = TL::X32;
-  constexpr int FE = X32 ? 8 : 4;
-  using FragT = typename Frag<X32>::type;
-  using L = BwdLds<TL>;
-  constexpr int CMAX = L::CMAX;
-  constexpr int NQ = (CMAX * ROWS + THREADS - 1) / THREADS;
-  constexpr int NV = (CMAX * V + THREADS - 1) / THREADS;
-
-  int unit, part;
-  if (!map_block<TL::P>(a.B * a.N, unit, part)) return;
-  const int T = a.T, N = a.N, C = a.C;
-  const int b = unit / N, n = unit - b * N;
-  const int g = n / (N / a.Nqk);
-  const int tid = threadIdx.x, lane = tid & 63;
-  // wave-level indices as scalars: branches on them must be real (uniform) branches, because
-  // a matrix-core instruction that is merely predicated off still executes
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int rb = wave / CT, ct = wave - rb * CT;
-  const int jl = lane & 15, ig = lane >> 4;
-  const int col0 = ct * 16, rowb = rb * 16;
-  const int row_base = part * ROWS;
-
-  extern __shared__ __attribute__((aligned(16))) char lds[];
-  typedef _Float16 XRow2[LDH2];
-  typedef _Float16 XRow[LDH];
-  XRow2 *Hx = (XRow2 *)(lds + L::X);                // phase A view: [2*ROWS][LDH2], (hi, lo) pairs
-  XRow *Dx = (XRow *)(lds + L::X);                  // phase B view: [2*ROWS][LDH], fp16 dS
-  f4_t *fin = (f4_t *)(lds + L::X);                 // phase ends: [2][WAVES][64] partial accumulators
-  h4_t *stH = (h4_t *)(lds + L::SH);                // [C][RB][CT][64]
-  h4_t *stZ = (h4_t *)(lds + L::SZ);
-  float *kS = (float *)(lds + L::KS_);
-  float *qS = (float *)(lds + L::QS_);
-  float *vS = (float *)(lds + L::VS_);
-  float *dyS = (float *)(lds + L::DYS_);
-  _Float16 *kH = (_Float16 *)(lds + L::KH_);
-  _Float16 *vH = (_Float16 *)(lds + L::VH_);
-  _Float16 *dyH = (_Float16 *)(lds + L::DYH_);
-  float *fS = (float *)(lds + L::FS_);
-
-  const bf16_raw *__restrict__ qg = (const bf16_raw *)a.q;
-  const bf16_raw *__restrict__ kg = (const bf16_raw *)a.k;
-  const bf16_raw *__restrict__ vg = (const bf16_raw *)a.v;
-  const bf16_raw *__restrict__ dyg = (const bf16_raw *)a.dy;
-  const float *__restrict__ fg = a.f;
-
-  // ---- W fragments.
-  //  wf : recompute, B[k][n = j]: k-slots 2e, 2e+1 of MFMA m hold W[16 m + 4 ig + e][col0 + jl]
-  //       (they meet the (hi, lo) pair of that state element);
-  //  wtf: carry contraction with W^T, B[k = j][n = c] = W[col0 + jl][j]
-  h8_t wf[CT];
-  FragT wtf[KS];
-  {
-    const bf16_raw *Wn = (const bf16_raw *)a.W + (size_t)n * V * V;
-#pragma unroll
-    for (int m = 0; m < CT; ++m)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int c = 16 * m + 4 * ig + e;
-        const _Float16 w = (_Float16)bf16_to_f32(Wn[(size_t)c * V + col0 + jl]);
-        wf[m][2 * e] = w;
-        wf[m][2 * e + 1] = w;
-      }
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-      for (int e = 0; e < FE; ++e) {
-        const int kk = FE * ig + e + 32 * ks;
-        wtf[ks][e] = (_Float16)bf16_to_f32(Wn[(size_t)(col0 + jl) * V + kk]);
-      }
-  }
-
-  const size_t tile_off = (size_t)(row_base + rowb + 4 * ig) * V + col0 + jl;
-  const size_t st_off = (size_t)unit * K * V + tile_off;
-  float carry[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) carry[r] = a.dHT ? a.dHT[st_off + (size_t)r * V] : 0.f;
-  f4_t dWacc[CT];
-#pragma unroll
-  for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = f4_t{0.f, 0.f, 0.f, 0.f};
-
-  const int nck = (T + C - 1) / C;
-  const f4_t zero4 = {0.f, 0.f, 0.f, 0.f};
-
-  // ---- staging: a whole chunk of q, k, v, dy, f goes through registers to LDS;
-  //      the loads for chunk ck-1 are issued before phase B of chunk ck.
-  bf16_raw rq[NQ], rk[NQ], rv[NV], rdy[NV];
-  float rf = 1.f;
-  float hck[4];
-  auto stage_load = [&](int ck) {
-    const int t0 = ck * C;
-    const int len = (T - t0) < C ? (T - t0) : C;
-#pragma unroll
-    for (int m = 0; m < NQ; ++m) {
-      const int idx = tid + m * THREADS;
-      const int s = idx / ROWS, i = idx - s * ROWS;
-      const bool ok = s < len;
-      const size_t off = (((size_t)b * T + (t0 + s)) * a.Nqk + g) * K + row_base + i;
-      rq[m] = ok ? qg[off] : (bf16_raw)0;
-      rk[m] = ok ? kg[off] : (bf16_raw)0;
-    }
-#pragma unroll
-    for (int m = 0; m < NV; ++m) {
-      const int idx = tid + m * THREADS;
-      const int s = idx / V, j = idx - s * V;
-      const bool ok = s < len;
-      const size_t off = (((size_t)b * T + (t0 + s)) * N + n) * V + j;
-      rv[m] = ok ? vg[off] : (bf16_raw)0;
-      rdy[m] = ok ? dyg[off] : (bf16_raw)0;
-    }
-    rf = (tid < len) ? fg[((size_t)b * T + (t0 + tid)) * N + n] : 1.f;
-    const float *src = a.ckpt + ((size_t)unit * nck + ck) * K * V + tile_off;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) hck[r] = src[(size_t)r * V];
-  };
-  auto stage_store = [&]() {
-    // keep the conversions here: hoisted to the loads they would wait for the loads at once
-#pragma unroll
-    for (int m = 0; m < NQ; ++m) asm volatile("" : "+v"(rq[m]), "+v"(rk[m]));
-#pragma unroll
-    for (int m = 0; m < NV; ++m) asm volatile("" : "+v"(rv[m]), "+v"(rdy[m]));
-    asm volatile("" : "+v"(rf), "+v"(hck[0]), "+v"(hck[1]), "+v"(hck[2]), "+v"(hck[3]));
-#pragma unroll
-    for (int m = 0; m < NQ; ++m) {
-      const int idx = tid + m * THREADS;
-      if (idx < CMAX * ROWS) {
-        const float kf = bf16_to_f32(rk[m]);
-        kS[idx] = kC * kf;
-        kH[idx] = (_Float16)kf;
-        qS[idx] = bf16_to_f32(rq[m]);
-      }
-    }
-#pragma unroll
-    for (int m = 0; m < NV; ++m) {
-      const int idx = tid + m * THREADS;
-      if (idx < CMAX * V) {
-        const float vf = bf16_to_f32(rv[m]), dyf = bf16_to_f32(rdy[m]);
-        vS[idx] = vf;
-        vH[idx] = (_Float16)vf;
-        dyS[idx] = dyf;
-        dyH[2 * idx] = (_Float16)dyf;
-        dyH[2 * idx + 1] = (_Float16)dyf;
-      }
-    }
-    if (tid < CMAX) {
-      fS[tid * 4 + 0] = rf;
-      fS[tid * 4 + 1] = kC * (1.f - rf);
-      fS[tid * 4 + 2] = 1.f - rf;
-      fS[tid * 4 + 3] = -2.f * (kC * (1.f - rf));
-    }
-  };
-
-  // dq of chunk step s_col (= H after that step, times dy of that step): this wave adds
-  // its k-slice (columns of tile ct) into accumulator column s_col.
-  auto dq_slice = [&](f4_t acc, const h8_t &af_ct, int s_col) {
-    h8_t bf = *(const h8_t *)&dyH[s_col * 2 * V + 2 * (16 * ct + 4 * ig)];
-    if (jl != s_col) bf = h8_t{0, 0, 0, 0, 0, 0, 0, 0};
-    return mfma_k32(af_ct, bf, acc);
-  };
-
-  if (nck > 0) stage_load(nck - 1);
-
-  for (int ck = nck - 1; ck >= 0; --ck) {
-    const int t0 = ck * C;
-    const int len = (T - t0) < C ? (T - t0) : C;
-
-    // ================= phase A: recompute the chunk, fill the stash
-    stage_store();
-    float h[4];
-    uint32_t pk[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      h[r] = kC * hck[r];
-      pk[r] = split_hi_lo(h[r]);
-    }
-    int cur = 0;
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-      *(uint32_t *)&Hx[cur * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
-    lds_barrier();
-    f4_t dqacc = zero4;  // D[m = i][n = s]: dq of chunk step s, this wave's k-slice
-
-    for (int s = 0; s < len; ++s) {
-      // ---- R: contraction (and this wave's slice of dq of the previous step)
-      h8_t af[CT];
-#pragma unroll
-      for (int m = 0; m < CT; ++m)
-        af[m] = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * m + 4 * ig)];
-      const float f = fS[s * 4 + 0], gp = fS[s * 4 + 1], m2g = fS[s * 4 + 3];
-      const f4_t k4 = *(const f4_t *)&kS[s * ROWS + rowb + 4 * ig];
-      const float vj = vS[s * V + col0 + jl];
-      f4_t acc = zero4;
-#pragma unroll
-      for (int m = 0; m < CT; ++m) acc = mfma_k32(af[m], wf[m], acc);
-      settle(acc);
-
-      // ---- E: tanh, gate, stash, write back
-      stH[((s * RB + rb) * CT + ct) * 64 + lane] = hi_of_pairs(pk);  // hi(H'_{t-1}), this tile
-      h4_t zp;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        // same operations, in the same order, as the forward kernel
-        const float t1 = fmaf(f, h[r], gp);
-        const float sp = fmaf(k4[r], vj, acc[r]);
-        const float e = __builtin_amdgcn_exp2f(sp);
-        const float rr = __builtin_amdgcn_rcpf(1.f + e);
-        const float z = fmaf(-2.f * kC, rr, kC);  // c tanh(s)
-        h[r] = fmaf(m2g, rr, t1);
-        zp[r] = (_Float16)z;
-        pk[r] = split_hi_lo(h[r]);
-      }
-      stZ[((s * RB + rb) * CT + ct) * 64 + lane] = zp;
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        *(uint32_t *)&Hx[(cur ^ 1) * ROWS + rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
-      if (s > 0) {  // dq slice of the previous step; af still holds the state after it
-                    // (compile-time index per branch keeps af[] in registers)
-#pragma unroll
-        for (int m = 0; m < CT; ++m)
-          if (ct == m) dqacc = dq_slice(dqacc, af[m], s - 1);
-      }
-      lds_barrier();
-      cur ^= 1;
-    }
-    {  // dq of the chunk's last step, from the state after it
-      const h8_t afl = *(const h8_t *)&Hx[cur * ROWS + rowb + jl][2 * (16 * ct + 4 * ig)];
-      dqacc = dq_slice(dqacc, afl, len - 1);
-    }
-    lds_barrier();  // all reads of the exchange buffer are done: it now carries partials
-    fin[wave * 64 + lane] = dqacc;
-    lds_barrier();
-    if (ct == 0 && jl < len) {  // lane (ig, jl): rows rowb + 4 ig + r of chunk step jl
-      f4_t d = fin[(rb * CT + 0) * 64 + lane];
-#pragma unroll
-      for (int c2 = 1; c2 < CT; ++c2) d += fin[(rb * CT + c2) * 64 + lane];
-      d *= kInvC;
-      const int t = t0 + jl;
-      if (ws.dqh)
-        *(f4_t *)&ws.dqh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
-      else
-        *(uint2 *)&((bf16_raw *)a.dq)[(((size_t)b * T + t) * a.Nqk + g) * K + row_base + rowb +
-                                      4 * ig] = pack4_bf16(d);
-    }
-    lds_barrier();  // the exchange buffer is reused for dS from here on
-
-    // ================= phase B: reverse sweep over the chunk
-    // this chunk's vectors stay in LDS; the next chunk's are fetched into registers
-    if (ck > 0) stage_load(ck - 1);
-    cur = 0;
-    f4_t dkacc = zero4;  // D[m = i][n = s]   (waves ct < KS: one 32-column slice each)
-    f4_t dvacc = zero4;  // D[m = s][n = j]   partial over this row block
-    f4_t dfacc = zero4;  // D[m][n = s]       16 partial sums of df of step s
-
-    // stash and vector reads of a step are issued one step ahead (they do not depend on the sweep)
-    struct StepIn {
-      float f, gm, dyj;
-      f4_t q4;
-      h4_t zp, hown, kfr;
-      h4_t hfr[CT];
-    };
-    auto load_step = [&](int s) {
-      StepIn in;
-      in.f = fS[s * 4 + 0];
-      in.gm = fS[s * 4 + 2];
-      in.q4 = *(const f4_t *)&qS[s * ROWS + rowb + 4 * ig];
-      in.dyj = dyS[s * V + col0 + jl];
-      in.zp = stZ[((s * RB + rb) * CT + ct) * 64 + lane];
-#pragma unroll
-      for (int c2 = 0; c2 < CT; ++c2) in.hfr[c2] = stH[((s * RB + rb) * CT + c2) * 64 + lane];
-      // this wave's own tile again (indexing hfr[] with the runtime ct would turn into selects)
-      in.hown = stH[((s * RB + rb) * CT + ct) * 64 + lane];
-      in.kfr = *(const h4_t *)&kH[s * ROWS + rowb + 4 * ig];
-      return in;
-    };
-    StepIn nxt = load_step(len - 1);
-
-    for (int s = len - 1; s >= 0; --s) {
-      // ---- E1: G and dS
-      const StepIn in = nxt;
-      const float f = in.f, gm = in.gm;
-      const bool mine = jl == s;  // this lane's accumulator column / row belongs to step s
-
-      float G[4];
-      h4_t dsp;
-      float dfl = 0.f;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float zz = (float)in.zp[r];
-        const float hh = (float)in.hown[r];
-        G[r] = fmaf(in.q4[r], in.dyj, carry[r]);
-        dfl = fmaf(G[r], hh - zz, dfl);
-        const float u = fmaf(zz * (-kInvC * kInvC), zz, 1.f);  // 1 - tanh^2
-        const float ds = (gm * G[r]) * u;
-        dsp[r] = (_Float16)ds;
-      }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) Dx[cur * ROWS + rowb + 4 * ig + r][col0 + jl] = dsp[r];
-      if (s > 0) nxt = load_step(s - 1);
-      lds_barrier();
-
-      // ---- R2: carry = f G + dS W^T, while the matrix core also takes the row contractions
-      FragT af[KS];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        af[ks] = *(const FragT *)&Dx[cur * ROWS + rowb + jl][FE * ig + 32 * ks];
-      // dW' += H'^T dS  (this wave: all c tiles x its own j tile, rows of its row block)
-#pragma unroll
-      for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = mfma_k16(in.hfr[c2], dsp, dWacc[c2]);
-      {  // dv_s[j] = sum_i k_i dS[i][j]: A[m][k = i] = k_i in row m == s only
-        h4_t kfr = in.kfr;
-        if (!mine) kfr = h4_t{0, 0, 0, 0};
-        dvacc = mfma_k16(kfr, dsp, dvacc);
-      }
-      {  // df_s = sum G (H' - Z') / c: the lane partial enters as a bf16 pair (hi, lo) in two
-         // k-slots against ones in column s; the MFMA adds the four lane groups
-        const uint32_t ub = __builtin_bit_cast(uint32_t, dfl);
-        const float lo = dfl - __builtin_bit_cast(float, ub & 0xFFFF0000u);
-        uint2 av;
-        av.x = (ub >> 16) | (__builtin_bit_cast(uint32_t, lo) & 0xFFFF0000u);
-        av.y = 0u;
-        uint2 bv;
-        bv.x = mine ? 0x3F803F80u : 0u;  // bf16 1.0 twice
-        bv.y = 0u;
-        typedef short s4_t __attribute__((ext_vector_type(4)));
-        dfacc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s4_t, av),
-                                                          __builtin_bit_cast(s4_t, bv), dfacc, 0,
-                                                          0, 0);
-      }
-      f4_t d = zero4;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        if constexpr (X32)
-          d = mfma_k32(af[ks], wtf[ks], d);
-        else
-          d = mfma_k16(af[ks], wtf[ks], d);
-      }
-      settle(d);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) carry[r] = fmaf(f, G[r], d[r]);
-      if (ct < KS) {  // dk_s = dS v_s into accumulator column s (one 32-column slice per wave)
-        FragT bf = *(const FragT *)&vH[s * V + FE * ig + 32 * ct];
-        if (!mine) {
-          if constexpr (X32)
-            bf = FragT{0, 0, 0, 0, 0, 0, 0, 0};
-          else
-            bf = FragT{0, 0, 0, 0};
-        }
-        // (af is indexed with a compile-time slice per branch to stay in registers)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          if (ct == ks) {
-            if constexpr (X32)
-              dkacc = mfma_k32(af[ks], bf, dkacc);
-            else
-              dkacc = mfma_k16(af[ks], bf, dkacc);
-          }
-      }
-      cur ^= 1;
-    }
-
-    // ---- end of the chunk: add the waves' partial accumulators through LDS and store
-    lds_barrier();  // every read of the exchange buffer, the stash and the vectors is done
-    fin[wave * 64 + lane] = dkacc;
-    fin[(WAVES + wave) * 64 + lane] = dvacc;
-    {  // df: 4 registers, then the four lane groups (lane jl of each holds step jl)
-      float x = (dfacc[0] + dfacc[1]) + (dfacc[2] + dfacc[3]);
-      x += __shfl_xor(x, 16, 64);
-      x += __shfl_xor(x, 32, 64);
-      if (lane < 16 && jl < len)
-        ws.dfp[((size_t)(part * WAVES + wave) * a.B * T + (size_t)b * T + t0 + jl) * N + n] =
-            x * kInvC;
-    }
-    lds_barrier();
-    if (ct == 0 && jl < len) {  // dk: lane (ig, jl): rows rowb + 4 ig + r of chunk step jl
-      f4_t d = fin[(rb * CT + 0) * 64 + lane];
-#pragma unroll
-      for (int ks = 1; ks < KS; ++ks) d += fin[(rb * CT + ks) * 64 + lane];
-      const int t = t0 + jl;
-      if (ws.dkh)
-        *(f4_t *)&ws.dkh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
-      else
-        *(uint2 *)&((bf16_raw *)a.dk)[(((size_t)b * T + t) * a.Nqk + g) * K + row_base + rowb +
-                                      4 * ig] = pack4_bf16(d);
-    }
-    if (rb == 0) {  // dv: lane (ig, jl): column col0 + jl of chunk steps 4 ig + r
-      f4_t d = fin[(WAVES + 0 * CT + ct) * 64 + lane];
-#pragma unroll
-      for (int r2 = 1; r2 < RB; ++r2) d += fin[(WAVES + r2 * CT + ct) * 64 + lane];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int sc = 4 * ig + r;
-        if (sc < len) {
-          const size_t off = (((size_t)b * T + t0 + sc) * N + n) * V + col0 + jl;
-          if constexpr (TL::P == 1)
-            ((bf16_raw *)a.dv)[off] = f32_to_bf16(d[r]);
-          else
-            ws.dvp[(size_t)part * a.B * T * N * V + off] = d[r];
-        }
-      }
-    }
-    lds_barrier();  // partial buffer free; next chunk restages the vectors
-  }
-
-  if (a.dH0)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) a.dH0[st_off + (size_t)r * V] = carry[r];
-  // dW partial of this (unit, part, row block): rows c = 16 c2 + 4 ig + r, column col0 + jl
-  {
-    float *dst = ws.dWp + (((size_t)unit * TL::P + part) * RB + rb) * V * V;
-#pragma unroll
-    for (int c2 = 0; c2 < CT; ++c2)
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        dst[(size_t)(c2 * 16 + 4 * ig + r) * V + col0 + jl] = dWacc[c2][r] * kInvC;
-  }
-}
-
-// ---------------------------------------------------------------------------
-// Overlapped variant: the recompute of chunk c-1 and the reverse sweep of chunk c
-// run at the same time in one workgroup.
-//
-// Recomputing a chunk needs only its checkpoint, so it does not have to wait
-// for the sweep of the chunk after it.  The workgroup holds two teams of WAVES
-// wavefronts: team A recomputes chunk c-1 into one half of a double-buffered
-// stash while team B sweeps chunk c out of the other half.  Both teams run
-// the same per-step code as the sequential kernel above and meet at one
-// workgroup barrier per step, which both need anyway for their own LDS
-// exchange.  The step chain of either phase is mostly LDS / barrier / MFMA
-// latency, so with twice the waves per SIMD the vector ALU is simply busy for
-// a larger share of the same time: a chunk costs about one phase, not two.
-// The stash is half as deep (two buffers), so checkpoints are twice as dense.
+// LDS carve-up of the kernel.  The stash is double buffered (one half per team), which
+// bounds the checkpoint interval C.
 template <typename TL>
 struct OvLds {
   static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, LDH2 = TL::LDH2, RB = TL::RB,
@@ -516,15 +58,15 @@ struct OvLds {
   static constexpr int HX_BYTES = 2 * ROWS * LDH * 2;     // team A exchange, fp16 state
   static constexpr int DX_BYTES = 2 * ROWS * LDH * 2;     // team B exchange, fp16 dS
   static constexpr int STASH_STEP = RB * CT * 64 * 8;     // one h4 per lane per tile
-  static constexpr int VEC_A = ROWS * 4 + V * 4 + V * 4 + 16;          // c*k, v, dy twice (f16), f
+  static constexpr int VEC_A = ROWS * 4 + V * 4 + V * 4 + 16;          // c*k, v, dy (f16, padded), f
   static constexpr int VEC_B = ROWS * 4 + V * 4 + ROWS * 2 + V * 2 + 16;  // q, dy, k f16, v f16, f
   static constexpr int PER_STEP = 4 * STASH_STEP + VEC_A + VEC_B;
   static constexpr int FIXED = HX_BYTES + DX_BYTES;
   static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 448) / PER_STEP;
-  static constexpr int CMAX = CMAX_RAW > 8 ? 8 : CMAX_RAW;  // two chunks share 16 accumulator columns
-  // usable: both teams fit the workgroup and the register file, the stash holds a few steps,
-  // and team B's stash half can hold its end-of-chunk partials
-  static constexpr bool OK = (2 * WAVES <= 16) && (V <= 64) && (CMAX >= 4) &&
+  static constexpr int CMAX = CMAX_RAW > 8 ? 8 : CMAX_RAW;  // (a step is one of 16 accumulator columns)
+  // usable: both teams fit one workgroup, the stash holds a few steps, and the buffers that
+  // carry the end-of-chunk partials are large enough for them
+  static constexpr bool OK = (2 * WAVES <= 16) && (CMAX >= 4) &&
                              (CMAX * 2 * STASH_STEP >= 2 * WAVES * 1024) &&
                              (HX_BYTES >= WAVES * 1024);
   static constexpr int C_ = CMAX > 0 ? CMAX : 1;
@@ -534,8 +76,8 @@ struct OvLds {
   // immediate of the LDS instructions (one base register instead of one per step)
   static constexpr int KS_ = DX + DX_BYTES;                // team A: float c*k [C][ROWS]
   static constexpr int VS_ = KS_ + C_ * ROWS * 4;          //         float v   [C][V]
-  static constexpr int DYH_ = VS_ + C_ * V * 4;            //         half dy twice [C][2V]
-  static constexpr int FA_ = DYH_ + C_ * V * 4;            //         float f, c(1-f), -, -2c(1-f)
+  static constexpr int DYH_ = VS_ + C_ * V * 4;            //         half dy (scaled per step) [C][V]
+  static constexpr int FA_ = DYH_ + C_ * V * 4;            //         float f, c(1-f), 1/dy-scale of the two half rows
   static constexpr int QS_ = FA_ + C_ * 16;                // team B: float q   [C][ROWS]
   static constexpr int DYS_ = QS_ + C_ * ROWS * 4;         //         float dy  [C][V]
   static constexpr int KH_ = DYS_ + C_ * V * 4;            //         half k    [C][ROWS]
@@ -661,19 +203,21 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         // dy_s enters the dq contraction as fp16: each step's row is scaled by a power of two
         // so that its largest entry lands in [2^10, 2^11) (loss-scaled or token-averaged
         // gradients are far outside the fp16 range); column s of dq is scaled back at the end
+        // (a row of V = 128 has two halves of 64 columns with a scale each: a dq slice
+        //  covers 32 columns, i.e. lies inside one half)
+        constexpr int GRP = V < 64 ? V : 64;
         const bool in = idx < CMAX * V;
         const float dyf = in ? bf16_to_f32(rdy[m]) : 0.f;
-        const int e = ilog2f(fminf(fmaxf(group_max_nonneg<V>(fabsf(dyf)), 1e-30f), 1e30f));
+        const int e = ilog2f(fminf(fmaxf(group_max_nonneg<GRP>(fabsf(dyf)), 1e-30f), 1e30f));
         if (in) {
           vS[idx] = bf16_to_f32(rv[m]);
           dyH[idx] = (_Float16)(dyf * pow2i(10 - e));
-          if (idx % V == 0) fA[(idx / V) * 4 + 2] = pow2i(e - 10);
+          if (idx % GRP == 0) fA[(idx / V) * 4 + 2 + (idx % V) / 64] = pow2i(e - 10);
         }
       }
       if (tid < CMAX) {
         fA[tid * 4 + 0] = rf;
         fA[tid * 4 + 1] = kC * (1.f - rf);
-        fA[tid * 4 + 3] = -2.f * (kC * (1.f - rf));
       }
     };
     // dq of chunk step s_col (= H after that step, times dy of that step): wave ct < KS adds
@@ -718,7 +262,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
           af[ks] = *(const FragT *)&Hx[rd * ROWS + rowb + jl][FE * ig + 32 * ks];
-        const float f = fA[s * 4 + 0], gp = fA[s * 4 + 1], m2g = fA[s * 4 + 3];
+        const float f = fA[s * 4 + 0], gp = fA[s * 4 + 1], m2g = -2.f * gp;
         const f4_t k4 = *(const f4_t *)&kS[s * ROWS + rowb + 4 * ig];
         const float vj = vS[s * V + col0 + jl];
         f4_t acc = zero4;
@@ -775,10 +319,12 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       if (active) fin[wave * 64 + lane] = dqacc;
       lds_barrier();  // E2
       if (active && ct == 0 && jl < len) {
-        f4_t d = fin[(rb * CT + 0) * 64 + lane];
+        // add the 32-column slices, each scaled back by its step's (and half row's) dy scale
+        f4_t d = fin[(rb * CT + 0) * 64 + lane] * fA[jl * 4 + 2];
 #pragma unroll
-        for (int ks = 1; ks < KS; ++ks) d += fin[(rb * CT + ks) * 64 + lane];
-        d *= kInvC * fA[jl * 4 + 2];  // undo this step's dy scale
+        for (int ks = 1; ks < KS; ++ks)
+          d += fin[(rb * CT + ks) * 64 + lane] * fA[jl * 4 + 2 + (32 * ks) / 64];
+        d *= kInvC;
         const int t = t0 + jl;
         if (ws.dqh)
           *(f4_t *)&ws.dqh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
@@ -976,10 +522,15 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       const f4_t q4 = lds_ld<f4_t>(bR4, L::QS_ + s * ROWS * 4);
       const float dyj = sc * lds_ld<float>(bC4, L::DYS_ + s * V * 4);
       const h4_t zp = lds_ld<h4_t>(bO, (CMAX + s) * L::STASH_STEP);
+      // (with 8 column tiles the register file cannot hold all H tiles next to the step's
+      //  other operands: they are then fetched right before their MFMAs, see below)
+      constexpr bool EARLY_H = CT <= 4;
       h4_t hfr[CT];
+      if constexpr (EARLY_H) {
 #pragma unroll
-      for (int c2 = 0; c2 < CT; ++c2)
-        hfr[c2] = lds_ld<h4_t>(bH, s * L::STASH_STEP + c2 * 512);
+        for (int c2 = 0; c2 < CT; ++c2)
+          hfr[c2] = lds_ld<h4_t>(bH, s * L::STASH_STEP + c2 * 512);
+      }
       const h4_t hown = lds_ld<h4_t>(bO, s * L::STASH_STEP);
       const bool mine = jlB == s;
       // k_s in row s of the A operand only: the other lanes read zeros
@@ -1011,7 +562,10 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       for (int r = 0; r < 4; ++r)
         lds_st<_Float16>(bDw, L::DX + (wr * ROWS + r) * LDH * 2, dsp[r]);
 #pragma unroll
-      for (int c2 = 0; c2 < CT; ++c2) dWacc[c2] = mfma_k16(hfr[c2], dsp, dWacc[c2]);
+      for (int c2 = 0; c2 < CT; ++c2) {
+        if constexpr (!EARLY_H) hfr[c2] = lds_ld<h4_t>(bH, s * L::STASH_STEP + c2 * 512);
+        dWacc[c2] = mfma_k16(hfr[c2], dsp, dWacc[c2]);
+      }
       dvacc = mfma_k16(kfr, dsp, dvacc);
       // df_s = sum G (H' - Z') / c: fp32 MFMA against ones in column s adds the four lane
       // groups; the 16 rows of that column are added at the end of the chunk
@@ -1177,7 +731,7 @@ WsLayout bwd_ws_layout(int B, int T, int N, int Nqk, int K, int V, int P, int RB
 
 template <typename TL>
 hipError_t launch_bwd(const BwdArgs &a, hipStream_t s) {
-  using L = BwdLds<TL>;
+  static_assert(OvLds<TL>::OK, "tile does not fit the two-team kernel");
   const int units = a.B * a.N;
   const WsLayout w = bwd_ws_layout(a.B, a.T, a.N, a.Nqk, a.K, a.V, TL::P, TL::RB);
   BwdWs ws;
@@ -1189,21 +743,12 @@ hipError_t launch_bwd(const BwdArgs &a, hipStream_t s) {
   ws.dkh = shared ? (float *)(a.ws + w.dkh) : nullptr;
   hipError_t e;
   if (units > 0) {
-    if constexpr (OvLds<TL>::OK) {
-      if (a.C > OvLds<TL>::CMAX) return hipErrorInvalidValue;
-      e = hipFuncSetAttribute((const void *)mfma_bwd_overlap_kernel<TL>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, OvLds<TL>::BYTES);
-      if (e != hipSuccess) return e;
-      hipLaunchKernelGGL(mfma_bwd_overlap_kernel<TL>, dim3(grid_blocks(units, TL::P)),
-                         dim3(2 * TL::THREADS), OvLds<TL>::BYTES, s, a, ws);
-    } else {
-      if (a.C > L::CMAX) return hipErrorInvalidValue;
-      e = hipFuncSetAttribute((const void *)mfma_bwd_kernel<TL>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
-      if (e != hipSuccess) return e;
-      hipLaunchKernelGGL(mfma_bwd_kernel<TL>, dim3(grid_blocks(units, TL::P)), dim3(TL::THREADS),
-                         L::BYTES, s, a, ws);
-    }
+    if (a.C > OvLds<TL>::CMAX) return hipErrorInvalidValue;
+    e = hipFuncSetAttribute((const void *)mfma_bwd_overlap_kernel<TL>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, OvLds<TL>::BYTES);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(mfma_bwd_overlap_kernel<TL>, dim3(grid_blocks(units, TL::P)),
+                       dim3(2 * TL::THREADS), OvLds<TL>::BYTES, s, a, ws);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (a.T > 0) {
       {
@@ -1260,8 +805,7 @@ int mfma_bwd_max_chunk(int K, int V) {
   int best = kChunkCap;
 #define X(K_, V_, RB_) \
   if (K == K_ && V == V_) {                                                                 \
-    const int c = OvLds<Tile<K_, V_, RB_>>::OK ? OvLds<Tile<K_, V_, RB_>>::CMAX             \
-                                               : BwdLds<Tile<K_, V_, RB_>>::CMAX;           \
+    const int c = OvLds<Tile<K_, V_, RB_>>::CMAX;                                          \
     if (c < best) best = c;                                                                \
   }
   M2RNN_TILE_CASES(X)

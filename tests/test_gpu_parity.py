@@ -170,7 +170,7 @@ def test_saturated_tanh_bf16():
     gu.compare(got, ref, gu.TOL["bf16"], label="saturated")
 
 
-@pytest.mark.parametrize("K,V", [(64, 64), (32, 32), (64, 16), (16, 16)])
+@pytest.mark.parametrize("K,V", [(64, 64), (32, 32), (64, 16), (16, 16), (128, 128)])
 @pytest.mark.parametrize("scale", [2.0 ** -24, 2.0 ** 18])
 def test_gradient_dynamic_range_bf16(K, V, scale):
     """dy and dH_T far outside the fp16 range (token-averaged losses give ~1e-7, loss scaling
