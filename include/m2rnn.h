@@ -29,6 +29,11 @@
  *   - Results are bit-reproducible: all cross-workgroup sums (over state rows,
  *     over heads that share q/k, over the batch for dW) are done in a fixed
  *     order, without atomics (the paper's Algorithm 2 uses atomic adds).
+ *   - Numeric range with M2RNN_BF16: q, k, v, W and the state feed fp16
+ *     matrix-core operands, so their magnitudes must stay below 2*10^4 (the
+ *     recurrence itself keeps |H| <= max(1, |H0|)).  dy, dHT and the gradients
+ *     may have any fp32 magnitude: the backward rescales them by powers of two
+ *     internally.  With M2RNN_F32 everything is plain fp32.
  */
 #ifndef M2RNN_H_
 #define M2RNN_H_

@@ -53,7 +53,7 @@ __device__ __forceinline__ uint2 pack4_bf16(f4_t x) {
 // bounds the checkpoint interval C.
 template <typename TL>
 struct OvLds {
-  static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, LDH2 = TL::LDH2, RB = TL::RB,
+  static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, RB = TL::RB,
                        CT = TL::CT, WAVES = TL::WAVES;
   static constexpr int HX_BYTES = 2 * ROWS * LDH * 2;     // team A exchange, fp16 state
   static constexpr int DX_BYTES = 2 * ROWS * LDH * 2;     // team B exchange, fp16 dS
@@ -93,7 +93,7 @@ struct OvLds {
 template <typename TL>
 __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdArgs a, BwdWs ws) {
   constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS, KS = TL::KS,
-                LDH = TL::LDH, LDH2 = TL::LDH2, WAVES = TL::WAVES;
+                LDH = TL::LDH, WAVES = TL::WAVES;
   constexpr int THREADS = TL::THREADS;  // per team
   constexpr bool X32 = TL::X32;
   constexpr int FE = X32 ? 8 : 4;
