@@ -359,7 +359,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   // [2^8, 2^9): a factor 2^7 of growth inside the chunk still fits, small values keep
   // their mantissa.  Powers of two make the scaling exact; outputs are divided by sc.
   float sc = 1.f, isc = 1.f;
-  float *scl = (float *)(lds + L::SCL_);
+  int set_now = 0;
+  int *scl = (int *)(lds + L::SCL_);  // two sets of { max |carry|, max |q|, max |dy| } bit patterns,
+                                       // by iteration parity; filled with LDS atomic max
   auto wave_max = [&](float x) { return group_max_nonneg<64>(x); };
 
   bf16_raw rq[NQ], rk[NQ], rv[NV], rdy[NV];
@@ -415,9 +417,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       for (int m = 0; m < NV; ++m) md = fmaxf(md, fabsf(bf16_to_f32(rdy[m])));
       mq = wave_max(mq);
       md = wave_max(md);
-      if (lane == 0) {
-        scl[8 + wave] = mq;
-        scl[16 + wave] = md;
+      if (lane == 0) {  // (non-negative floats order like their bit patterns)
+        atomicMax(&scl[4 * set_now + 1], __builtin_bit_cast(int, mq));
+        atomicMax(&scl[4 * set_now + 2], __builtin_bit_cast(int, md));
       }
     }
     if (tid < CMAX) {
@@ -437,22 +439,17 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     const int t0 = ck * C;
     const int len = active ? ((T - t0) < C ? (T - t0) : C) : 0;
     const int buf = (it - 1) & 1;
+    set_now = it & 1;  // maxima that decide this chunk's scale
     if (active) {
       stage_store();
       if (ck > 0) stage_load(ck - 1);
     }
     lds_barrier();  // P: stash[buf] was completed by team A in the previous iteration
+    // the other set was read one iteration ago and is filled again from the end of this one
+    if (wave == 0 && lane < 4) scl[4 * (set_now ^ 1) + lane] = 0;
     if (active) {  // scale of this chunk (wave-uniform, identical in every wave of the team)
-      float mc = 0.f, mq = 0.f, md = 0.f;
-#pragma unroll
-      for (int w4 = 0; w4 < (WAVES + 3) / 4; ++w4) {  // slots of absent waves hold zero
-        const f4_t xc = *(const f4_t *)&scl[4 * w4], xq = *(const f4_t *)&scl[8 + 4 * w4],
-                   xd = *(const f4_t *)&scl[16 + 4 * w4];
-        mc = fmaxf(mc, fmaxf(fmaxf(xc[0], xc[1]), fmaxf(xc[2], xc[3])));
-        mq = fmaxf(mq, fmaxf(fmaxf(xq[0], xq[1]), fmaxf(xq[2], xq[3])));
-        md = fmaxf(md, fmaxf(fmaxf(xd[0], xd[1]), fmaxf(xd[2], xd[3])));
-      }
-      const int e = ilog2f(fminf(fmaxf(mc + mq * md, 1e-30f), 1e30f));
+      const f4_t mx = __builtin_bit_cast(f4_t, *(const u4_t *)&scl[4 * set_now]);  // |carry|, |q|, |dy|
+      const int e = ilog2f(fminf(fmaxf(mx[0] + mx[1] * mx[2], 1e-30f), 1e30f));
       const float sc_new = pow2i(8 - e);
       const float ratio = sc_new * isc;  // exact: both are powers of two
       sc = sc_new;
@@ -593,7 +590,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     {  // largest true |carry| of this wave, for the next chunk's scale
       float mc = fmaxf(fmaxf(fabsf(carry[0]), fabsf(carry[1])), fmaxf(fabsf(carry[2]), fabsf(carry[3])));
       mc = wave_max(mc) * isc;
-      if (lane == 0) scl[wave] = mc;
+      if (lane == 0) atomicMax(&scl[4 * (set_now ^ 1)], __builtin_bit_cast(int, mc));
     }
     lds_barrier();  // E1: all reads of this chunk's stash half are done: it takes the partials
     f4_t *fin = (f4_t *)(lds + L::ST + (buf * 2) * CMAX * L::STASH_STEP);
