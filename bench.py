@@ -41,19 +41,21 @@ def alu_slots(kind):
 
 
 def cpu_baseline(wl, inp):
-    """The float64 oracle, as it stands, on a bounded sample of the workload:
-    whole (batch, head) recurrences at full T for as many heads as it takes to
-    give every host thread one recurrence."""
+    """The float64 oracle, as it stands, on a bounded sample of the workload
+    (about 15 s of CPU work): whole (batch, head) recurrences of the first few
+    heads, at full T where one head fits the budget."""
     import oracle
     from paper_2603_14360_amd.synth_inputs import select_heads
     threads = oracle.num_threads()
-    heads = max(1, min(wl.N, -(-threads // wl.B)))
-    # keep the sample to roughly 10-30 s: shorten T for the big-state workloads
+    # size the sample for roughly 15 s.  The oracle runs one (batch, head) recurrence per
+    # thread, so the sample is a whole number of "rounds" of `threads` recurrences; if one
+    # recurrence alone takes longer than ~25 s, a prefix of the sequence is used
+    per_unit = lambda T: T * wl.K * wl.V * wl.V * (10 if wl.backward else 3) / 4e9   # seconds
     T = wl.T
-    cost = wl.B * heads * T * wl.K * wl.V * wl.V / max(1, threads)
-    while cost > 6e9 and T > 256:
+    while per_unit(T) > 25.0 and T > 256:
         T //= 2
-        cost /= 2
+    rounds = max(1, int(15.0 // max(per_unit(T), 1e-9)))
+    heads = int(max(1, min(wl.N, (rounds * max(1, threads)) // wl.B)))
     sub = select_heads(inp, list(range(heads)))
     for n in ("q", "k", "v", "f", "dy"):
         sub[n] = sub[n][:, :T]
