@@ -185,3 +185,27 @@ def test_gradient_dynamic_range_bf16(K, V, scale):
     got = gu.run_gpu(inp, "bf16")
     ref = gu.run_oracle(inp)
     _report(label, gu.compare(got, ref, gu.TOL["bf16"], label=label))
+
+
+@pytest.mark.parametrize("K,V,Nqk", [(64, 64, 0), (64, 16, 1)])
+def test_single_step_decode_chain_bf16(K, V, Nqk):
+    """Recurrent inference: T = 1 per call, the state handed from call to call (H_T -> H0),
+    for a batch of sequences; every step's y and the final state against the oracle's one
+    long run."""
+    B, N, steps = 24, 4, 20
+    wl = Workload("t", B, steps, N, K, V, "bf16", 123 + V, K ** -0.5, 2.0, use_H0=True, Nqk=Nqk)
+    inp = make_inputs(wl)
+    ref = gu.run_oracle(inp, backward=False)
+    H = inp["H0"]
+    ys = []
+    for t in range(steps):
+        one = {n: (x[:, t:t + 1] if (x is not None and n in ("q", "k", "v", "f", "dy")) else x)
+               for n, x in inp.items()}
+        one["H0"] = H
+        out = gu.run_gpu(one, "bf16", backward=False)
+        ys.append(out["y"])
+        H = out["HT"].astype(np.float32)
+    y = np.concatenate(ys, axis=1)
+    errs = {"y": gu.rel_err(y, ref["y"]), "HT": gu.rel_err(H.astype(np.float64), ref["HT"])}
+    _report("decode K%d V%d" % (K, V), errs)
+    assert errs["y"] <= gu.TOL["bf16"] and errs["HT"] <= gu.TOL["bf16"], errs
