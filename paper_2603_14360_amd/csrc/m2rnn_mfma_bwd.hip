@@ -7,10 +7,9 @@
 // workgroup holds two teams of wavefronts that run at the same time:
 //   team A  recomputes chunk c-1 forward from its checkpoint, parking for every
 //           step the fp16 state before the step (H'_{t-1} = c H_{t-1}) and
-//           Z'_t = c tanh(.) in one half of the double-buffered stash, and
-//           accumulates dq_t = H_t dy_t;
-//   team B  sweeps chunk c in reverse out of the other half: no tanh and no
-//           state contraction are recomputed there.
+//           Z'_t = c tanh(.) in the stash, and accumulates dq_t = H_t dy_t;
+//   team B  sweeps chunk c in reverse out of the stash entries team A made one
+//           iteration earlier: no tanh and no state contraction are recomputed.
 // Recomputing a chunk needs only its checkpoint, so it does not wait for the
 // sweep of the chunk after it.  Both teams meet at one workgroup barrier per
 // step, which each needs anyway for its own LDS exchange.
@@ -49,27 +48,37 @@ __device__ __forceinline__ uint2 pack4_bf16(f4_t x) {
   return p;
 }
 
-// LDS carve-up of the kernel.  The stash is double buffered (one half per team), which
-// bounds the checkpoint interval C.
+// LDS carve-up of the kernel.
+//
+// The stash holds C + 1 step slots for BOTH teams, used as two stacks that grow towards
+// each other: in an iteration team A pushes the C steps of its chunk in time order from one
+// end while team B pops the steps of its chunk, which were pushed from the other end one
+// iteration earlier, in reverse order.  The slot B reads in a step is the one A fills in
+// the next step, so one spare slot is enough and the checkpoint interval C can be almost
+// twice what two separate buffers would allow (chunk boundaries cost several step times).
 template <typename TL>
 struct OvLds {
-  static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, RB = TL::RB,
-                       CT = TL::CT, WAVES = TL::WAVES;
-  static constexpr int HX_BYTES = 2 * ROWS * LDH * 2;     // team A exchange, fp16 state
-  static constexpr int DX_BYTES = 2 * ROWS * LDH * 2;     // team B exchange, fp16 dS
+  static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, RB = TL::RB, CT = TL::CT,
+                       WAVES = TL::WAVES, KS = TL::KS;
+  static constexpr int XCH = 2 * ROWS * LDH * 2;          // a double-buffered fp16 exchange tile set
+  // the exchange buffers also carry the end-of-chunk partials (1 KB per contributing wave):
+  // dq slices of team A and dk slices of team B in A's buffer, dv of team B in B's buffer
+  static constexpr int HX_BYTES = XCH > 2 * RB * KS * 1024 ? XCH : 2 * RB * KS * 1024;
+  static constexpr int DX_BYTES = XCH > WAVES * 1024 ? XCH : WAVES * 1024;
   static constexpr int STASH_STEP = RB * CT * 64 * 8;     // one h4 per lane per tile
+  static constexpr int SLOT = 2 * STASH_STEP;             // a step slot: H' tiles, then Z' tiles
   static constexpr int VEC_A = ROWS * 4 + V * 4 + V * 4 + 16;          // c*k, v, dy (f16, padded), f
   static constexpr int VEC_B = ROWS * 4 + V * 4 + ROWS * 2 + V * 2 + 16;  // q, dy, k f16, v f16, f
-  static constexpr int PER_STEP = 4 * STASH_STEP + VEC_A + VEC_B;
-  static constexpr int FIXED = HX_BYTES + DX_BYTES;
-  static constexpr int CMAX_RAW = (kLdsLimit - FIXED - 448) / PER_STEP;
-  static constexpr int CMAX = CMAX_RAW > 8 ? 8 : CMAX_RAW;  // (a step is one of 16 accumulator columns)
-  // usable: both teams fit one workgroup, the stash holds a few steps, and the buffers that
-  // carry the end-of-chunk partials are large enough for them
-  static constexpr bool OK = (2 * WAVES <= 16) && (CMAX >= 4) &&
-                             (CMAX * 2 * STASH_STEP >= 2 * WAVES * 1024) &&
-                             (HX_BYTES >= WAVES * 1024);
+  static constexpr int PER_STEP = SLOT + VEC_A + VEC_B;
+  static constexpr int FIXED = HX_BYTES + DX_BYTES + SLOT + 448;
+  static constexpr int CMAX_RAW = (kLdsLimit - FIXED) / PER_STEP;
+  // per-tile cap: V = 128 stages twice the vectors per thread with a longer chunk (register
+  // spills); the one-wave teams of V = 16 lose resident workgroups to a larger LDS footprint
+  static constexpr int CCAP = V >= 128 ? 8 : (TL::THREADS <= 64 ? 12 : kChunkCap);
+  static constexpr int CMAX = CMAX_RAW > CCAP ? CCAP : CMAX_RAW;
+  static constexpr bool OK = (2 * WAVES <= 16) && (CMAX >= 4);
   static constexpr int C_ = CMAX > 0 ? CMAX : 1;
+  static constexpr int NSLOT = C_ + 1;
   static constexpr int HX = 0;
   static constexpr int DX = HX + HX_BYTES;
   // the small per-step vectors sit below the stash: their offsets then fit the 16-bit
@@ -84,9 +93,9 @@ struct OvLds {
   static constexpr int VH_ = KH_ + C_ * ROWS * 2;          //         half v    [C][V]
   static constexpr int FB_ = VH_ + C_ * V * 2;             //         f; f16x2 -(1-f)/c^2; f16x2 (1-f); -
   static constexpr int ZERO_ = FB_ + C_ * 16;              // 32 zero bytes (masked operand reads)
-  static constexpr int SCL_ = ZERO_ + 32;                  // team B: per-wave maxima [3][8] floats
-  static constexpr int ST = (SCL_ + 96 + 255) & ~255;      // [2][ {H, Z} ][C][RB][CT][64] h4
-  static constexpr int BYTES = ST + 4 * C_ * STASH_STEP;
+  static constexpr int SCL_ = ZERO_ + 32;                  // team B: maxima, two sets of 4 words
+  static constexpr int ST = (SCL_ + 96 + 255) & ~255;      // [NSLOT][ {H, Z} ][RB][CT][64] h4
+  static constexpr int BYTES = ST + NSLOT * SLOT;
   static_assert(!OK || BYTES <= kLdsLimit, "LDS overflow");
 };
 
@@ -122,8 +131,8 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   typedef _Float16 XRow[LDH];
   XRow *Hx = (XRow *)(lds + L::HX);
   XRow *Dx = (XRow *)(lds + L::DX);
-  auto stH = [&](int buf) { return (h4_t *)(lds + L::ST + (buf * 2 + 0) * CMAX * L::STASH_STEP); };
-  auto stZ = [&](int buf) { return (h4_t *)(lds + L::ST + (buf * 2 + 1) * CMAX * L::STASH_STEP); };
+  // slot of chunk step s for a chunk pushed in an iteration of parity p (see OvLds)
+  auto slot_of = [&](int s, int p) { return p ? (L::NSLOT - 1 - s) : s; };
   float *kS = (float *)(lds + L::KS_);
   float *vS = (float *)(lds + L::VS_);
   _Float16 *dyH = (_Float16 *)(lds + L::DYH_);
@@ -237,7 +246,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       const int ck = nck - 1 - it;
       const int t0 = ck * C;
       const int len = active ? ((T - t0) < C ? (T - t0) : C) : 0;
-      const int buf = it & 1;
+      const int par = it & 1;  // this chunk's end of the stash
       float h[4];
       h4_t hp;  // fp16 copy of the state before the current step (stash entry, MFMA operand)
       int cur = 0;
@@ -274,7 +283,8 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
             acc = mfma_k16(af[ks], wf[ks], acc);
         }
         settle(acc);
-        stH(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = hp;
+        h4_t *slot = (h4_t *)(lds + L::ST + slot_of(s, par) * L::SLOT) + (rb * CT + ct) * 64 + lane;
+        slot[0] = hp;
         h4_t zp;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -287,7 +297,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
           zp[r] = (_Float16)z;
           hp[r] = (_Float16)h[r];
         }
-        stZ(buf)[((s * RB + rb) * CT + ct) * 64 + lane] = zp;
+        slot[L::STASH_STEP / 8] = zp;
 #pragma unroll
         for (int r = 0; r < 4; ++r) Hx[wr * ROWS + rowb + 4 * ig + r][col0 + jl] = hp[r];
         if (s > 0 && ct < KS) {  // dq slice of the previous step; af still holds the state after it
@@ -315,15 +325,15 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         dqacc = dq_slice(dqacc, afl, len - 1);
       }
       lds_barrier();  // E1: exchange buffer free, it carries the dq partials now
-      f4_t *fin = (f4_t *)(lds + L::HX);
-      if (active) fin[wave * 64 + lane] = dqacc;
+      f4_t *fin = (f4_t *)(lds + L::HX);  // [RB][KS][64]: only the waves ct < KS hold a dq slice
+      if (active && ct < KS) fin[(rb * KS + ct) * 64 + lane] = dqacc;
       lds_barrier();  // E2
       if (active && ct == 0 && jl < len) {
         // add the 32-column slices, each scaled back by its step's (and half row's) dy scale
-        f4_t d = fin[(rb * CT + 0) * 64 + lane] * fA[jl * 4 + 2];
+        f4_t d = fin[(rb * KS + 0) * 64 + lane] * fA[jl * 4 + 2];
 #pragma unroll
         for (int ks = 1; ks < KS; ++ks)
-          d += fin[(rb * CT + ks) * 64 + lane] * fA[jl * 4 + 2 + (32 * ks) / 64];
+          d += fin[(rb * KS + ks) * 64 + lane] * fA[jl * 4 + 2 + (32 * ks) / 64];
         d *= kInvC;
         const int t = t0 + jl;
         if (ws.dqh)
@@ -438,13 +448,13 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     const int ck = nck - it;
     const int t0 = ck * C;
     const int len = active ? ((T - t0) < C ? (T - t0) : C) : 0;
-    const int buf = (it - 1) & 1;
+    const int par = (it - 1) & 1;  // the end of the stash this chunk was pushed from
     set_now = it & 1;  // maxima that decide this chunk's scale
     if (active) {
       stage_store();
       if (ck > 0) stage_load(ck - 1);
     }
-    lds_barrier();  // P: stash[buf] was completed by team A in the previous iteration
+    lds_barrier();  // P: this chunk's stash entries were completed by team A in the previous iteration
     // the other set was read one iteration ago and is filled again from the end of this one
     if (wave == 0 && lane < 4) scl[4 * (set_now ^ 1) + lane] = 0;
     if (active) {  // scale of this chunk (wave-uniform, identical in every wave of the team)
@@ -465,10 +475,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     // LDS addressing of this team: a few per-lane base offsets, made opaque once per chunk so
     // that they are not hoisted out of the chunk loop as one register per (array, step);
     // every access below is base + compile-time immediate in the unrolled sweep.
-    constexpr int HALF = 2 * CMAX * L::STASH_STEP;  // one stash buffer: H part, then Z part
     lchar *const l0 = (lchar *)lds;
-    lchar *bH = l0 + (L::ST + buf * HALF + rb * CT * 512 + lane * 8);  // stash H, tile 0 of my row block
-    lchar *bO = bH + ct * 512;                                // my own tile (H; Z at + CMAX steps)
+    lchar *bH = l0 + (L::ST + rb * CT * 512 + lane * 8);      // stash slot 0: H, tile 0 of my row block
+    lchar *bO = bH + ct * 512;                                // my own tile (H; Z one STASH_STEP later)
     lchar *bR4 = l0 + (rowb + 4 * ig) * 4;                    // q rows (fp32)
     lchar *bR2 = l0 + (rowb + 4 * ig) * 2;                    // k rows (fp16)
     lchar *bC4 = l0 + (col0 + jl) * 4;                        // dy column (fp32)
@@ -518,7 +527,8 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       const u2_t m4u = {fu[1], fu[1]}, g4u = {fu[2], fu[2]};  // -(1-f)/c^2 and (1-f), four times each
       const f4_t q4 = lds_ld<f4_t>(bR4, L::QS_ + s * ROWS * 4);
       const float dyj = sc * lds_ld<float>(bC4, L::DYS_ + s * V * 4);
-      const h4_t zp = lds_ld<h4_t>(bO, (CMAX + s) * L::STASH_STEP);
+      const int so = slot_of(s, par) * L::SLOT;  // byte offset of this step's slot
+      const h4_t zp = lds_ld<h4_t>(bO + so, L::STASH_STEP);
       // (with 8 column tiles the register file cannot hold all H tiles next to the step's
       //  other operands: they are then fetched right before their MFMAs, see below)
       constexpr bool EARLY_H = CT <= 4;
@@ -526,9 +536,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       if constexpr (EARLY_H) {
 #pragma unroll
         for (int c2 = 0; c2 < CT; ++c2)
-          hfr[c2] = lds_ld<h4_t>(bH, s * L::STASH_STEP + c2 * 512);
+          hfr[c2] = lds_ld<h4_t>(bH + so, c2 * 512);
       }
-      const h4_t hown = lds_ld<h4_t>(bO, s * L::STASH_STEP);
+      const h4_t hown = lds_ld<h4_t>(bO + so, 0);
       const bool mine = jlB == s;
       // k_s in row s of the A operand only: the other lanes read zeros
       const h4_t kfr = lds_ld<h4_t>(mine ? bR2 + (L::KH_ + s * ROWS * 2) : bZero + L::ZERO_, 0);
@@ -560,7 +570,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         lds_st<_Float16>(bDw, L::DX + (wr * ROWS + r) * LDH * 2, dsp[r]);
 #pragma unroll
       for (int c2 = 0; c2 < CT; ++c2) {
-        if constexpr (!EARLY_H) hfr[c2] = lds_ld<h4_t>(bH, s * L::STASH_STEP + c2 * 512);
+        if constexpr (!EARLY_H) hfr[c2] = lds_ld<h4_t>(bH + so, c2 * 512);
         dWacc[c2] = mfma_k16(hfr[c2], dsp, dWacc[c2]);
       }
       dvacc = mfma_k16(kfr, dsp, dvacc);
@@ -592,11 +602,13 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       mc = wave_max(mc) * isc;
       if (lane == 0) atomicMax(&scl[4 * (set_now ^ 1)], __builtin_bit_cast(int, mc));
     }
-    lds_barrier();  // E1: all reads of this chunk's stash half are done: it takes the partials
-    f4_t *fin = (f4_t *)(lds + L::ST + (buf * 2) * CMAX * L::STASH_STEP);
+    lds_barrier();  // E1: every read of the exchange buffers is done: they take the partials
+    // partials: dk slices behind team A's dq slices in A's exchange buffer, dv in B's own
+    f4_t *fink = (f4_t *)(lds + L::HX) + RB * KS * 64;  // [RB][KS][64]
+    f4_t *finv = (f4_t *)(lds + L::DX);                 // [WAVES][64]
     if (active) {
-      fin[wave * 64 + lane] = dkacc * isc;
-      fin[(WAVES + wave) * 64 + lane] = dvacc * isc;
+      if (ct < KS) fink[(rb * KS + ct) * 64 + lane] = dkacc * isc;
+      finv[wave * 64 + lane] = dvacc * isc;
       float x = (dfacc[0] + dfacc[1]) + (dfacc[2] + dfacc[3]);
       x += __shfl_xor(x, 16, 64);
       x += __shfl_xor(x, 32, 64);
@@ -607,9 +619,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     lds_barrier();  // E2
     if (active) {
       if (ct == 0 && jl < len) {
-        f4_t d = fin[(rb * CT + 0) * 64 + lane];
+        f4_t d = fink[(rb * KS + 0) * 64 + lane];
 #pragma unroll
-        for (int ks = 1; ks < KS; ++ks) d += fin[(rb * CT + ks) * 64 + lane];
+        for (int ks = 1; ks < KS; ++ks) d += fink[(rb * KS + ks) * 64 + lane];
         const int t = t0 + jl;
         if (ws.dkh)
           *(f4_t *)&ws.dkh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
@@ -618,9 +630,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
                                         4 * ig] = pack4_bf16(d);
       }
       if (rb == 0) {
-        f4_t d = fin[(WAVES + 0 * CT + ct) * 64 + lane];
+        f4_t d = finv[(0 * CT + ct) * 64 + lane];
 #pragma unroll
-        for (int r2 = 1; r2 < RB; ++r2) d += fin[(WAVES + r2 * CT + ct) * 64 + lane];
+        for (int r2 = 1; r2 < RB; ++r2) d += finv[(r2 * CT + ct) * 64 + lane];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int sc = 4 * ig + r;
