@@ -172,6 +172,14 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     bf16_raw rk[NQ], rv[NV], rdy[NV];
     float rf = 1.f;
     float hck[4];
+    // Global addresses of the staged vectors: a wave-uniform 64-bit base per tensor (batch
+    // element, head) plus a 32-bit element offset = per-thread constant + chunk start * row
+    // stride.  (One batch element of a tensor stays far below 2^32 elements.)
+    const bf16_raw *const kbase = kg + ((size_t)b * T * a.Nqk + g) * K + row_base;
+    const bf16_raw *const vbase = vg + ((size_t)b * T * N + n) * V;
+    const bf16_raw *const dybase = dyg + ((size_t)b * T * N + n) * V;
+    const float *const fbase = fg + (size_t)b * T * N + n;
+    const uint32_t kstride = (uint32_t)a.Nqk * K, vstride = (uint32_t)N * V;
     auto stage_load = [&](int ck) {
       const int t0 = ck * C;
       const int len = (T - t0) < C ? (T - t0) : C;
@@ -179,18 +187,17 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       for (int m = 0; m < NQ; ++m) {
         const int idx = tid + m * THREADS;
         const int s = idx / ROWS, i = idx - s * ROWS;
-        rk[m] = s < len ? kg[(((size_t)b * T + (t0 + s)) * a.Nqk + g) * K + row_base + i]
-                        : (bf16_raw)0;
+        rk[m] = s < len ? kbase[(uint32_t)t0 * kstride + ((uint32_t)s * kstride + i)] : (bf16_raw)0;
       }
 #pragma unroll
       for (int m = 0; m < NV; ++m) {
         const int idx = tid + m * THREADS;
         const int s = idx / V, j = idx - s * V;
-        const size_t off = (((size_t)b * T + (t0 + s)) * N + n) * V + j;
-        rv[m] = s < len ? vg[off] : (bf16_raw)0;
-        rdy[m] = s < len ? dyg[off] : (bf16_raw)0;
+        const uint32_t off = (uint32_t)t0 * vstride + ((uint32_t)s * vstride + j);
+        rv[m] = s < len ? vbase[off] : (bf16_raw)0;
+        rdy[m] = s < len ? dybase[off] : (bf16_raw)0;
       }
-      rf = (tid < len) ? fg[((size_t)b * T + (t0 + tid)) * N + n] : 1.f;
+      rf = (tid < len) ? fbase[(uint32_t)(t0 + tid) * (uint32_t)N] : 1.f;
       const float *src = a.ckpt + ((size_t)unit * nck + ck) * K * V + tile_off;
 #pragma unroll
       for (int r = 0; r < 4; ++r) hck[r] = src[(size_t)r * V];
@@ -376,6 +383,13 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
 
   bf16_raw rq[NQ], rk[NQ], rv[NV], rdy[NV];
   float rf = 1.f;
+  // (addresses as in team A: uniform base + 32-bit element offset)
+  const bf16_raw *const qbase = qg + ((size_t)b * T * a.Nqk + g) * K + row_base;
+  const bf16_raw *const kbase = kg + ((size_t)b * T * a.Nqk + g) * K + row_base;
+  const bf16_raw *const vbase = vg + ((size_t)b * T * N + n) * V;
+  const bf16_raw *const dybase = dyg + ((size_t)b * T * N + n) * V;
+  const float *const fbase = fg + (size_t)b * T * N + n;
+  const uint32_t kstride = (uint32_t)a.Nqk * K, vstride = (uint32_t)N * V;
   auto stage_load = [&](int ck) {
     const int t0 = ck * C;
     const int len = (T - t0) < C ? (T - t0) : C;
@@ -383,19 +397,19 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     for (int m = 0; m < NQ; ++m) {
       const int idx = tid + m * THREADS;
       const int s = idx / ROWS, i = idx - s * ROWS;
-      const size_t off = (((size_t)b * T + (t0 + s)) * a.Nqk + g) * K + row_base + i;
-      rq[m] = s < len ? qg[off] : (bf16_raw)0;
-      rk[m] = s < len ? kg[off] : (bf16_raw)0;
+      const uint32_t off = (uint32_t)t0 * kstride + ((uint32_t)s * kstride + i);
+      rq[m] = s < len ? qbase[off] : (bf16_raw)0;
+      rk[m] = s < len ? kbase[off] : (bf16_raw)0;
     }
 #pragma unroll
     for (int m = 0; m < NV; ++m) {
       const int idx = tid + m * THREADS;
       const int s = idx / V, j = idx - s * V;
-      const size_t off = (((size_t)b * T + (t0 + s)) * N + n) * V + j;
-      rv[m] = s < len ? vg[off] : (bf16_raw)0;
-      rdy[m] = s < len ? dyg[off] : (bf16_raw)0;
+      const uint32_t off = (uint32_t)t0 * vstride + ((uint32_t)s * vstride + j);
+      rv[m] = s < len ? vbase[off] : (bf16_raw)0;
+      rdy[m] = s < len ? dybase[off] : (bf16_raw)0;
     }
-    rf = (tid < len) ? fg[((size_t)b * T + (t0 + tid)) * N + n] : 1.f;
+    rf = (tid < len) ? fbase[(uint32_t)(t0 + tid) * (uint32_t)N] : 1.f;
   };
   auto stage_store = [&]() {
 #pragma unroll
