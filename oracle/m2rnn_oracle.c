@@ -11,8 +11,9 @@
  * Forward  : the recurrence equations of the paper's "M2RNN layer" section
  *            (Z_t = tanh(H_{t-1} W + k_t v_t^T); H_t = f_t H_{t-1} + (1-f_t) Z_t;
  *            y_t = H_t^T q_t), in the loop order of the forward algorithm
- *            (Algorithm 1).  The residual term w_r (.) v_t of the y equation is
- *            not part of the kernel in Algorithm 1 and is not computed here.
+ *            (Algorithm 1).  The residual term w_r (.) v_t of the y equation
+ *            (w_r: one weight per head and value channel) is added when w_r is
+ *            given; Algorithm 1 leaves it out, and so does a NULL w_r.
  * Backward : back-propagation through time as in the backward algorithm
  *            (Algorithm 2), with three readings of the printed listing:
  *              (1) the gradient of H_t is  q_t dy_t^T PLUS the gradient carried
@@ -23,6 +24,12 @@
  *            These readings are what the chain rule gives for the forward
  *            equations; the tests pin them with finite differences and with
  *            reverse-mode differentiation of an unrolled forward.
+ *            Per-step clipping of the state gradient (the paper's "Gradient
+ *            Clipping" paragraph names it without a rule): with clip > 0 every
+ *            element of the gradient handed from step t to step t-1 is clamped
+ *            to [-clip, clip] as soon as it is formed, i.e. before q dy^T of
+ *            step t-1 is added; dH0 is the clamped value; dHT is taken as
+ *            given.  clip <= 0 switches it off (exact gradients).
  *
  * Pins (tests/test_oracle_*.py): T=1 closed form, unrolled brute force,
  * finite differences, the Elman-RNN reduction of Theorem 1, the W=0 closed
@@ -31,7 +38,7 @@
  *
  * Layouts (dense, row-major, host memory, all double):
  *   q, k  [B,T,Nqk,K]   v, y, dy, dv [B,T,N,V]   f, df [B,T,N]
- *   W, dW [N,V,V]       H0, HT, dHT, dH0 [B,N,K,V]
+ *   W, dW [N,V,V]       H0, HT, dHT, dH0 [B,N,K,V]     w_r, dw_r [N,V]
  * Head n reads q/k head  n / (N/Nqk)  (Nqk = N: one q/k per head; Nqk = 1: the
  * paper's multi-value form where all heads share q and k).
  * K and V are NOT restricted to multiples of 16 here, so that tiny brute-force
@@ -82,7 +89,7 @@ static void step_forward(int K, int V, const double *W, const double *kt,
 int m2rnn_oracle_fwd(int B, int T, int N, int Nqk, int K, int V,
                      const double *q, const double *k, const double *v,
                      const double *f, const double *W, const double *H0,
-                     double *y, double *HT) {
+                     const double *w_r, double *y, double *HT) {
   if (B < 0 || T < 0 || N <= 0 || Nqk <= 0 || K <= 0 || V <= 0) return 1;
   if (N % Nqk != 0) return 1;
   const int heads_per_group = N / Nqk;
@@ -111,6 +118,7 @@ int m2rnn_oracle_fwd(int B, int T, int N, int Nqk, int K, int V,
         for (int j = 0; j < V; ++j) {
           double acc = 0.0;
           for (int i = 0; i < K; ++i) acc += H[i * V + j] * qt[i];
+          if (w_r) acc += w_r[(size_t)n * V + j] * v[IDX_V(b, t, n, j)];
           y[IDX_V(b, t, n, j)] = acc;
         }
       }
@@ -124,13 +132,14 @@ int m2rnn_oracle_fwd(int B, int T, int N, int Nqk, int K, int V,
 /* Backward (BPTT).  Every state of the forward run is kept in memory for the
  * unit being processed (T+1 matrices of K x V).  H0, dHT, dH0 may be NULL.
  * dq, dk are sums over the heads that share a q/k head, added in increasing
- * head order; dW is the sum over the batch, added in increasing b. */
+ * head order; dW is the sum over the batch, added in increasing b.
+ * w_r (with dw_r) may be NULL: no residual.  clip <= 0: no clipping. */
 int m2rnn_oracle_bwd(int B, int T, int N, int Nqk, int K, int V,
                      const double *q, const double *k, const double *v,
                      const double *f, const double *W, const double *H0,
-                     const double *dy, const double *dHT, double *dq,
-                     double *dk, double *dv, double *df, double *dW,
-                     double *dH0) {
+                     const double *w_r, double clip, const double *dy,
+                     const double *dHT, double *dq, double *dk, double *dv,
+                     double *df, double *dW, double *dH0, double *dw_r) {
   if (B < 0 || T < 0 || N <= 0 || Nqk <= 0 || K <= 0 || V <= 0) return 1;
   if (N % Nqk != 0) return 1;
   const int heads_per_group = N / Nqk;
@@ -216,6 +225,9 @@ int m2rnn_oracle_bwd(int B, int T, int N, int Nqk, int K, int V,
             for (int j = 0; j < V; ++j) acc += dS[i * V + j] * Wn[c * V + j];
             C[i * V + c] = ft * G[i * V + c] + acc;
           }
+        if (clip > 0.0)
+          for (size_t e = 0; e < KV; ++e)
+            C[e] = C[e] > clip ? clip : (C[e] < -clip ? -clip : C[e]);
         /* dW += H_{t-1}^T dS */
         for (int c = 0; c < V; ++c)
           for (int j = 0; j < V; ++j) {
@@ -233,6 +245,8 @@ int m2rnn_oracle_bwd(int B, int T, int N, int Nqk, int K, int V,
         for (int j = 0; j < V; ++j) {
           double acc = 0.0;
           for (int i = 0; i < K; ++i) acc += dS[i * V + j] * kt[i];
+          /* y_t also holds w_r (.) v_t */
+          if (w_r) acc += w_r[(size_t)n * V + j] * dyt[j];
           dv[IDX_V(b, t, n, j)] = acc;
         }
       }
@@ -259,6 +273,16 @@ int m2rnn_oracle_bwd(int B, int T, int N, int Nqk, int K, int V,
       for (int b = 0; b < B; ++b) s += dW_unit[((size_t)b * N + n) * V * V + e];
       dW[(size_t)n * V * V + e] = s;
     }
+  /* dw_r[n][j] = sum over b and t of dy (.) v */
+  if (w_r && dw_r)
+    for (int n = 0; n < N; ++n)
+      for (int j = 0; j < V; ++j) {
+        double s = 0.0;
+        for (int b = 0; b < B; ++b)
+          for (int t = 0; t < T; ++t)
+            s += dy[IDX_V(b, t, n, j)] * v[IDX_V(b, t, n, j)];
+        dw_r[(size_t)n * V + j] = s;
+      }
   free(dq_unit);
   free(dk_unit);
   free(dW_unit);

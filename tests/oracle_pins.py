@@ -77,11 +77,22 @@ def check_T1_closed_form(fwd, bwd, tol=1e-13):
 # Brute force: the forward unrolled with torch float64 tensor expressions and
 # differentiated by torch.autograd (a library's reverse mode, independent of
 # the hand-derived backward).
-def torch_unrolled(c, need_grad=True):
+def torch_unrolled(c, need_grad=True, clip=0.0):
+    """With "w_r" in the case the residual w_r (.) v_t is added to y_t.  clip > 0 clamps
+    the gradient that autograd sends along every recurrent edge (state handed from one
+    step to the next, and H0 to the first step); the readout of a state is not on it."""
     import torch
+    names = ("q", "k", "v", "f", "W", "H0") + (("w_r",) if "w_r" in c else ())
     t = {n: (None if c[n] is None else
              torch.tensor(c[n], dtype=torch.float64, requires_grad=need_grad))
-         for n in ("q", "k", "v", "f", "W", "H0")}
+         for n in names}
+
+    def edge(H):
+        if clip <= 0 or not need_grad or not H.requires_grad:
+            return H
+        Hc = H.clone()
+        Hc.register_hook(lambda g: g.clamp(-clip, clip))
+        return Hc
     B, T, Nqk, K = c["q"].shape
     N, V = c["v"].shape[2], c["v"].shape[3]
     per = N // Nqk
@@ -93,9 +104,13 @@ def torch_unrolled(c, need_grad=True):
             H = t["H0"][b, n] if t["H0"] is not None else torch.zeros(K, V, dtype=torch.float64)
             yn = []
             for s in range(T):
-                Z = torch.tanh(H @ t["W"][n] + torch.outer(t["k"][b, s, g], t["v"][b, s, n]))
-                H = t["f"][b, s, n] * H + (1 - t["f"][b, s, n]) * Z
-                yn.append(H.T @ t["q"][b, s, g])
+                Hp = edge(H)
+                Z = torch.tanh(Hp @ t["W"][n] + torch.outer(t["k"][b, s, g], t["v"][b, s, n]))
+                H = t["f"][b, s, n] * Hp + (1 - t["f"][b, s, n]) * Z
+                yt = H.T @ t["q"][b, s, g]
+                if "w_r" in t:
+                    yt = yt + t["w_r"][n] * t["v"][b, s, n]
+                yn.append(yt)
             yb.append(torch.stack(yn) if T > 0 else torch.zeros(0, V, dtype=torch.float64))
             Hb.append(H)
         ys.append(torch.stack(yb, dim=1))       # [T, N, V]
@@ -128,6 +143,55 @@ def check_unrolled_autograd(fwd, bwd, shapes=None, tol=1e-11):
             assert relerr(dW, g["W"]) < tol, "dW"
             if with_H0:
                 assert relerr(dH0, g["H0"]) < tol, "dH0"
+
+
+# --------------------------------------------------------------------------
+# The residual w_r (.) v_t of the y equation and per-step clipping of the state gradient.
+def check_residual_T1_closed_form(fwd, bwd, tol=1e-13):
+    c = rand_case(12, 2, 1, 3, 4, 5)
+    q, k, v, f, W, H0 = _args(c)
+    w_r = np.random.default_rng(5).standard_normal((3, 5))
+    y0, HT0 = fwd(q, k, v, f, W, H0)
+    y, HT = fwd(q, k, v, f, W, H0, w_r=w_r)
+    assert np.array_equal(HT, HT0)
+    assert relerr(y, y0 + w_r[None, None] * v) < tol
+    g0 = bwd(q, k, v, f, W, H0, c["dy"], c["dHT"])
+    g = bwd(q, k, v, f, W, H0, c["dy"], c["dHT"], w_r=w_r)
+    assert len(g) == 7
+    for i in (0, 1, 3, 4, 5):
+        assert np.array_equal(g[i], g0[i])
+    assert relerr(g[2], g0[2] + w_r[None, None] * c["dy"]) < tol
+    assert relerr(g[6], (c["dy"] * v).sum(axis=(0, 1))) < tol
+
+
+def check_residual_autograd(fwd, bwd, tol=1e-11):
+    for (B, N, T, K, V, Nqk) in [(2, 4, 3, 4, 3, 2), (1, 2, 5, 3, 4, None)]:
+        c = rand_case(300 + T, B, T, N, K, V, Nqk=Nqk)
+        c["w_r"] = np.random.default_rng(6).standard_normal((N, V))
+        y_t, HT_t, g = torch_unrolled(c)
+        y, HT = fwd(*_args(c), w_r=c["w_r"])
+        assert relerr(y, y_t) < tol and relerr(HT, HT_t) < tol
+        got = bwd(*_args(c), c["dy"], c["dHT"], w_r=c["w_r"])
+        for x, n in zip(got, ("q", "k", "v", "f", "W", "H0", "w_r")):
+            assert relerr(x, g[n]) < tol, n
+
+
+def check_clipped_backward(fwd, bwd, tol=1e-11):
+    for (B, N, T, K, V, Nqk) in [(2, 2, 6, 3, 4, None), (1, 4, 5, 4, 3, 1)]:
+        c = rand_case(400 + T, B, T, N, K, V, Nqk=Nqk)
+        c["dy"] = c["dy"] * 3.0
+        free = bwd(*_args(c), c["dy"], c["dHT"])
+        # a bound above every carried gradient changes nothing
+        same = bwd(*_args(c), c["dy"], c["dHT"], clip=1e6)
+        for a, b in zip(free, same):
+            assert np.array_equal(a, b)
+        clip = 0.25 * float(np.abs(free[5]).max())
+        got = bwd(*_args(c), c["dy"], c["dHT"], clip=clip)
+        assert np.abs(got[5]).max() <= clip          # dH0 is a clamped value
+        assert relerr(got[4], free[4]) > 1e-3        # and the bound was active
+        _, _, g = torch_unrolled(c, clip=clip)
+        for x, n in zip(got, ("q", "k", "v", "f", "W", "H0")):
+            assert relerr(x, g[n]) < tol, n
 
 
 # --------------------------------------------------------------------------
@@ -342,4 +406,5 @@ ALL_CHECKS = [
     check_adjoint_identity, check_elman_reduction, check_W_zero_closed_form,
     check_gate_limits, check_segment_chaining, check_row_and_column_structure,
     check_state_bound, check_backward_linearity, check_empty_sequence,
+    check_residual_T1_closed_form, check_residual_autograd, check_clipped_backward,
 ]

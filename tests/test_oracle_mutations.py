@@ -47,6 +47,19 @@ MUTATIONS = {
         ("acc += dS[i * V + j] * vt[j];", "acc += dS[i * V + j] * kt[i];"),
     "head_group_mapping":
         ("const int g = n / heads_per_group;", "const int g = n % Nqk;"),
+    "residual_without_v":
+        ("acc += w_r[(size_t)n * V + j] * v[IDX_V(b, t, n, j)];", "acc += w_r[(size_t)n * V + j];"),
+    "residual_missing_in_dv":
+        ("if (w_r) acc += w_r[(size_t)n * V + j] * dyt[j];", ""),
+    "dw_r_head_index":
+        ("dw_r[(size_t)n * V + j] = s;", "dw_r[(size_t)(N - 1 - n) * V + j] = s;"),
+    "clip_one_sided":
+        ("C[e] = C[e] > clip ? clip : (C[e] < -clip ? -clip : C[e]);",
+         "C[e] = C[e] > clip ? clip : C[e];"),
+    "clip_after_readout_term":
+        ("G[i * V + j] = qt[i] * dyt[j] + C[i * V + j];",
+         "{ G[i * V + j] = qt[i] * dyt[j] + C[i * V + j]; if (clip > 0.0) G[i * V + j] = "
+         "G[i * V + j] > clip ? clip : (G[i * V + j] < -clip ? -clip : G[i * V + j]); }"),
     "readout_before_update":
         ("acc += H[i * V + j] * qt[i];", "acc += S[i * V + j] * qt[i];"),
 }
