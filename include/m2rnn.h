@@ -136,6 +136,41 @@ m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k,
                        float *dW, float *dH0, void *workspace,
                        size_t workspace_bytes, void *hip_stream);
 
+/*
+ * The two options of the layer that sit on the scan itself (host struct; NULL = none).
+ *   w_r        residual weight of the y equation of the layer section,
+ *              y_t = H_t^T q_t + w_r (.) v_t : [N,V] io dtype, device memory, one weight per
+ *              head and value channel; NULL = no residual (Algorithm 1's kernel).  In the
+ *              backward the same w_r adds w_r (.) dy_t to dv_t, and dw_r receives
+ *              sum over b, t of dy (.) v.
+ *   dw_r       [N,V] fp32, device, out; read by m2rnn_bwd_opt only, required there when
+ *              w_r is given (M2RNN_ERR_NULL otherwise), ignored when w_r is NULL.
+ *   grad_clip  per-step clipping of the state gradient during BPTT (the paper's
+ *              "Gradient Clipping" paragraph, which gives no rule; the rule here): when
+ *              > 0, every element of the gradient that step t hands to step t-1
+ *              (f_t G_t + dS_t W^T) is clamped to [-grad_clip, grad_clip] as soon as it
+ *              is formed, before q dy^T of step t-1 is added; dH0 is the clamped value,
+ *              dHT is used as given.  <= 0: off, gradients are exact.  Forward ignores it.
+ */
+typedef struct {
+  const void *w_r;
+  float *dw_r;
+  float grad_clip;
+} m2rnn_opts;
+
+/* m2rnn_fwd / m2rnn_bwd with options; opts == NULL behaves exactly like the plain calls.
+ * All other arguments, the workspace sizes and the error behaviour are the same. */
+m2rnn_status m2rnn_fwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const void *q,
+                           const void *k, const void *v, const float *f, const void *W,
+                           const float *H0, void *y, float *HT, float *ckpt,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+m2rnn_status m2rnn_bwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const void *q,
+                           const void *k, const void *v, const float *f, const void *W,
+                           const float *H0, const float *ckpt, const void *dy,
+                           const float *dHT, void *dq, void *dk, void *dv, float *df,
+                           float *dW, float *dH0, void *workspace,
+                           size_t workspace_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

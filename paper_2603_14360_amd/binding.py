@@ -15,13 +15,18 @@ M2RNN_F32 = 0
 M2RNN_BF16 = 1
 
 EXPORTS = ("m2rnn_status_string", "m2rnn_default_chunk", "m2rnn_max_chunk",
-           "m2rnn_ckpt_bytes", "m2rnn_workspace_bytes", "m2rnn_fwd", "m2rnn_bwd")
+           "m2rnn_ckpt_bytes", "m2rnn_workspace_bytes", "m2rnn_fwd", "m2rnn_bwd",
+           "m2rnn_fwd_opt", "m2rnn_bwd_opt")
 
 
 class m2rnn_desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("T", ctypes.c_int32), ("N", ctypes.c_int32),
                 ("Nqk", ctypes.c_int32), ("K", ctypes.c_int32), ("V", ctypes.c_int32),
                 ("io", ctypes.c_int32), ("chunk", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+class m2rnn_opts(ctypes.Structure):
+    _fields_ = [("w_r", ctypes.c_void_p), ("dw_r", ctypes.c_void_p), ("grad_clip", ctypes.c_float)]
 
 
 class M2RNNError(RuntimeError):
@@ -60,6 +65,11 @@ def lib():
         L.m2rnn_fwd.argtypes = [dp] + [vp] * 10 + [sz, vp]
         L.m2rnn_bwd.restype = ctypes.c_int
         L.m2rnn_bwd.argtypes = [dp] + [vp] * 16 + [sz, vp]
+        op = ctypes.POINTER(m2rnn_opts)
+        L.m2rnn_fwd_opt.restype = ctypes.c_int
+        L.m2rnn_fwd_opt.argtypes = [dp, op] + [vp] * 10 + [sz, vp]
+        L.m2rnn_bwd_opt.restype = ctypes.c_int
+        L.m2rnn_bwd_opt.argtypes = [dp, op] + [vp] * 16 + [sz, vp]
         _lib = L
     return _lib
 
@@ -123,6 +133,35 @@ def m2rnn_bwd(desc, q, k, v, f, W, H0, ckpt, dy, dHT, dq, dk, dv, df, dW, dH0, w
     return rc
 
 
+def make_opts(w_r=None, dw_r=None, grad_clip=0.0):
+    """m2rnn_opts from torch tensors (or None)."""
+    return m2rnn_opts(None if w_r is None else w_r.data_ptr(),
+                      None if dw_r is None else dw_r.data_ptr(), float(grad_clip))
+
+
+def m2rnn_fwd_opt(desc, opts, q, k, v, f, W, H0, y, HT, ckpt, workspace, stream=None, check=True):
+    """m2rnn_fwd with an m2rnn_opts (None = no options)."""
+    rc = lib().m2rnn_fwd_opt(ctypes.byref(desc), None if opts is None else ctypes.byref(opts),
+                             _ptr(q), _ptr(k), _ptr(v), _ptr(f), _ptr(W), _ptr(H0), _ptr(y),
+                             _ptr(HT), _ptr(ckpt), _ptr(workspace), _nbytes(workspace),
+                             ctypes.c_void_p(stream or 0))
+    if check and rc != 0:
+        raise M2RNNError(rc, "m2rnn_fwd_opt")
+    return rc
+
+
+def m2rnn_bwd_opt(desc, opts, q, k, v, f, W, H0, ckpt, dy, dHT, dq, dk, dv, df, dW, dH0,
+                  workspace, stream=None, check=True):
+    rc = lib().m2rnn_bwd_opt(ctypes.byref(desc), None if opts is None else ctypes.byref(opts),
+                             _ptr(q), _ptr(k), _ptr(v), _ptr(f), _ptr(W), _ptr(H0), _ptr(ckpt),
+                             _ptr(dy), _ptr(dHT), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(df),
+                             _ptr(dW), _ptr(dH0), _ptr(workspace), _nbytes(workspace),
+                             ctypes.c_void_p(stream or 0))
+    if check and rc != 0:
+        raise M2RNNError(rc, "m2rnn_bwd_opt")
+    return rc
+
+
 # --------------------------------------------------------------------------
 # Buffer plumbing for callers that hold torch tensors: allocates outputs,
 # checkpoints and workspace with torch and calls the raw entry points on
@@ -158,13 +197,29 @@ class Scan:
     def _stream(self):
         return self.torch.cuda.current_stream().cuda_stream
 
-    def fwd(self, q, k, v, f, W, H0=None):
-        m2rnn_fwd(self.desc, q, k, v, f, W, H0, self.y, self.HT, self.ckpt, self.workspace,
-                  stream=self._stream())
+    def fwd(self, q, k, v, f, W, H0=None, w_r=None):
+        """w_r [N,V] (io dtype): adds the residual w_r (.) v_t to y_t."""
+        if w_r is None:
+            m2rnn_fwd(self.desc, q, k, v, f, W, H0, self.y, self.HT, self.ckpt, self.workspace,
+                      stream=self._stream())
+        else:
+            m2rnn_fwd_opt(self.desc, make_opts(w_r=w_r), q, k, v, f, W, H0, self.y, self.HT,
+                          self.ckpt, self.workspace, stream=self._stream())
         return self.y, self.HT
 
-    def bwd(self, q, k, v, f, W, H0, dy, dHT=None, use_ckpt=True):
-        m2rnn_bwd(self.desc, q, k, v, f, W, H0, self.ckpt if use_ckpt else None, dy, dHT,
-                  self.dq, self.dk, self.dv, self.df, self.dW, self.dH0, self.workspace,
-                  stream=self._stream())
-        return self.dq, self.dk, self.dv, self.df, self.dW, self.dH0
+    def bwd(self, q, k, v, f, W, H0, dy, dHT=None, use_ckpt=True, w_r=None, grad_clip=0.0):
+        """With w_r the result has a seventh entry, dw_r [N,V] fp32."""
+        ck = self.ckpt if use_ckpt else None
+        if w_r is None and not grad_clip > 0:
+            m2rnn_bwd(self.desc, q, k, v, f, W, H0, ck, dy, dHT, self.dq, self.dk, self.dv,
+                      self.df, self.dW, self.dH0, self.workspace, stream=self._stream())
+            return self.dq, self.dk, self.dv, self.df, self.dW, self.dH0
+        dw_r = None
+        if w_r is not None:
+            dw_r = self.torch.empty((self.desc.N, self.desc.V), dtype=self.torch.float32,
+                                    device=self.dW.device)
+        m2rnn_bwd_opt(self.desc, make_opts(w_r, dw_r, grad_clip), q, k, v, f, W, H0, ck, dy, dHT,
+                      self.dq, self.dk, self.dv, self.df, self.dW, self.dH0, self.workspace,
+                      stream=self._stream())
+        out = (self.dq, self.dk, self.dv, self.df, self.dW, self.dH0)
+        return out if dw_r is None else out + (dw_r,)

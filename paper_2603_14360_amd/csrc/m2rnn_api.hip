@@ -123,7 +123,8 @@ size_t m2rnn_workspace_bytes(const m2rnn_desc *desc, int bwd) {
   if (bwd) {
     // room for the backward's own checkpoint pass (used when ckpt == NULL)
     const size_t fwd_need = family_ws(desc, C, 0);
-    need = align256(need > fwd_need ? need : fwd_need) + align256(ckpt_bytes(desc, C));
+    need = align256(need > fwd_need ? need : fwd_need) + align256(ckpt_bytes(desc, C)) +
+           residual_dw_r_scratch_bytes(desc->N, desc->V);
   }
   return need;
 }
@@ -131,6 +132,14 @@ size_t m2rnn_workspace_bytes(const m2rnn_desc *desc, int bwd) {
 m2rnn_status m2rnn_fwd(const m2rnn_desc *desc, const void *q, const void *k, const void *v,
                        const float *f, const void *W, const float *H0, void *y, float *HT,
                        float *ckpt, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return m2rnn_fwd_opt(desc, nullptr, q, k, v, f, W, H0, y, HT, ckpt, workspace, workspace_bytes,
+                       hip_stream);
+}
+
+m2rnn_status m2rnn_fwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const void *q,
+                           const void *k, const void *v, const float *f, const void *W,
+                           const float *H0, void *y, float *HT, float *ckpt, void *workspace,
+                           size_t workspace_bytes, void *hip_stream) {
   m2rnn_status st = check_desc(desc);
   if (st != M2RNN_OK) return st;
   const int C = resolve_chunk(desc);
@@ -139,7 +148,8 @@ m2rnn_status m2rnn_fwd(const m2rnn_desc *desc, const void *q, const void *k, con
   const bool steps = !empty && desc->T > 0;
   if (!W) return M2RNN_ERR_NULL;
   if (steps && (!q || !k || !v || !f || !y)) return M2RNN_ERR_NULL;
-  const void *ptrs[] = {q, k, v, f, W, H0, y, HT, ckpt, workspace};
+  const void *w_r = opts ? opts->w_r : nullptr;
+  const void *ptrs[] = {q, k, v, f, W, H0, y, HT, ckpt, workspace, w_r};
   for (const void *p : ptrs)
     if (misaligned(p)) return M2RNN_ERR_ALIGN;
   const size_t need = family_ws(desc, C, 0);
@@ -151,6 +161,7 @@ m2rnn_status m2rnn_fwd(const m2rnn_desc *desc, const void *q, const void *k, con
   a.C = C; a.io = desc->io;
   a.q = q; a.k = k; a.v = v; a.W = W; a.f = f; a.H0 = H0;
   a.y = y; a.HT = HT; a.ckpt = ckpt; a.write_y = 1; a.ws = (char *)workspace;
+  a.w_r = w_r;
   hipStream_t s = (hipStream_t)hip_stream;
   const hipError_t e = run_fwd(desc, a, s);
   return e == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
@@ -161,6 +172,15 @@ m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k, con
                        const void *dy, const float *dHT, void *dq, void *dk, void *dv, float *df,
                        float *dW, float *dH0, void *workspace, size_t workspace_bytes,
                        void *hip_stream) {
+  return m2rnn_bwd_opt(desc, nullptr, q, k, v, f, W, H0, ckpt, dy, dHT, dq, dk, dv, df, dW, dH0,
+                       workspace, workspace_bytes, hip_stream);
+}
+
+m2rnn_status m2rnn_bwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const void *q,
+                           const void *k, const void *v, const float *f, const void *W,
+                           const float *H0, const float *ckpt, const void *dy, const float *dHT,
+                           void *dq, void *dk, void *dv, float *df, float *dW, float *dH0,
+                           void *workspace, size_t workspace_bytes, void *hip_stream) {
   m2rnn_status st = check_desc(desc);
   if (st != M2RNN_OK) return st;
   const int C = resolve_chunk(desc);
@@ -168,7 +188,11 @@ m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k, con
   const bool steps = desc->B > 0 && desc->T > 0;
   if (!W || !dW) return M2RNN_ERR_NULL;
   if (steps && (!q || !k || !v || !f || !dy || !dq || !dk || !dv || !df)) return M2RNN_ERR_NULL;
-  const void *ptrs[] = {q, k, v, f, W, H0, ckpt, dy, dHT, dq, dk, dv, df, dW, dH0, workspace};
+  const void *w_r = opts ? opts->w_r : nullptr;
+  float *dw_r = w_r ? opts->dw_r : nullptr;
+  if (w_r && !dw_r) return M2RNN_ERR_NULL;
+  const void *ptrs[] = {q,  k,  v,  f,  W,   H0,        ckpt, dy,  dHT,
+                        dq, dk, dv, df, dW, dH0, workspace, w_r,  dw_r};
   for (const void *p : ptrs)
     if (misaligned(p)) return M2RNN_ERR_ALIGN;
   const size_t need = m2rnn_workspace_bytes(desc, 1);
@@ -178,7 +202,8 @@ m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k, con
   hipStream_t s = (hipStream_t)hip_stream;
   const Family fam = family_of(desc);
   char *ws = (char *)workspace;
-  const size_t main_bytes = need - align256(ckpt_bytes(desc, C));
+  const size_t dwr_bytes = residual_dw_r_scratch_bytes(desc->N, desc->V);
+  const size_t main_bytes = need - align256(ckpt_bytes(desc, C)) - dwr_bytes;
   if (!ckpt && steps) {
     // The paper's pass 1, keeping one state per chunk: rerun the recurrence
     // from H0 without the readout, into the tail of the workspace.
@@ -188,6 +213,7 @@ m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k, con
     fa.V = desc->V; fa.C = C; fa.io = desc->io;
     fa.q = q; fa.k = k; fa.v = v; fa.W = W; fa.f = f; fa.H0 = H0;
     fa.y = nullptr; fa.HT = nullptr; fa.ckpt = own; fa.write_y = 0; fa.ws = ws;
+    fa.w_r = nullptr;
     const hipError_t e = run_fwd(desc, fa, s);
     if (e != hipSuccess) return M2RNN_ERR_HIP;
     ckpt = own;
@@ -197,7 +223,10 @@ m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k, con
   a.C = C; a.io = desc->io;
   a.q = q; a.k = k; a.v = v; a.W = W; a.dy = dy; a.f = f; a.H0 = H0; a.ckpt = ckpt; a.dHT = dHT;
   a.dq = dq; a.dk = dk; a.dv = dv; a.df = df; a.dW = dW; a.dH0 = dH0; a.ws = ws;
-  const hipError_t e = fam == kMfma ? mfma_bwd(a, s) : generic_bwd(a, s);
+  a.w_r = w_r; a.dw_r = dw_r; a.dwr_ws = (float *)(ws + need - dwr_bytes);
+  a.clip = opts ? opts->grad_clip : 0.f;
+  hipError_t e = fam == kMfma ? mfma_bwd(a, s) : generic_bwd(a, s);
+  if (e == hipSuccess && w_r) e = residual_dw_r(a, s);
   return e == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
 }
 

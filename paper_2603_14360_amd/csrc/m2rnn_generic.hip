@@ -135,6 +135,7 @@ __global__ void __launch_bounds__(kMaxThreads) gen_fwd_kernel(FwdArgs a, const f
       for (int j = tid; j < V; j += nt) {
         float acc = 0.f;
         for (int i = 0; i < K; ++i) acc = fmaf(Hs[i * V + j], qs[i], acc);
+        if (a.w_r) acc = fmaf(to_f32<IO>(((const IO *)a.w_r)[n * V + j]), vs[j], acc);
         y[v_off + j] = from_f32<IO>(acc);
       }
     }
@@ -274,6 +275,7 @@ __global__ void __launch_bounds__(kMaxThreads)
           float acc = 0.f;
           for (int j = 0; j < V; ++j) acc = fmaf(Xs[i * V + j], WTf[j * V + c], acc);
           carry[m] = fmaf(f, carry[m], acc);
+          if (a.clip > 0.f) carry[m] = fminf(fmaxf(carry[m], -a.clip), a.clip);
         }
       }
       // dW += H_{t-1}^T dS
@@ -299,6 +301,7 @@ __global__ void __launch_bounds__(kMaxThreads)
       for (int j = tid; j < V; j += nt) {
         float acc = 0.f;
         for (int i = 0; i < K; ++i) acc = fmaf(Xs[i * V + j], ks[i], acc);
+        if (a.w_r) acc = fmaf(to_f32<IO>(((const IO *)a.w_r)[n * V + j]), dys[j], acc);
         ((IO *)a.dv)[v_off + j] = from_f32<IO>(acc);
       }
       __syncthreads();
@@ -321,6 +324,29 @@ __global__ void dw_batch_sum_kernel(const float *dW_unit, float *dW, int B, int 
     for (int b = 0; b < B; ++b) s += dW_unit[(size_t)b * total + e];
     dW[e] = s;
   }
+}
+
+// Gradient of the residual weight: dw_r[n][j] = sum over (b, t) of dy (.) v.  Stage 1: block s
+// adds the rows r = s, s + S, s + 2S, ... of the [B*T, N*V] tensors in increasing r; stage 2
+// adds the S partial rows in increasing s.  The order is fixed, so the result is reproducible.
+constexpr int kDwrStages = 1024;
+template <typename IO>
+__global__ void dwr_stage1_kernel(const IO *__restrict__ dy, const IO *__restrict__ v,
+                                  float *__restrict__ part, size_t BT, int NV) {
+  for (int c = threadIdx.x; c < NV; c += blockDim.x) {
+    float acc = 0.f;
+    for (size_t r = blockIdx.x; r < BT; r += gridDim.x)
+      acc = fmaf(to_f32<IO>(dy[r * NV + c]), to_f32<IO>(v[r * NV + c]), acc);
+    part[(size_t)blockIdx.x * NV + c] = acc;
+  }
+}
+__global__ void dwr_stage2_kernel(const float *__restrict__ part, float *__restrict__ dw_r, int S,
+                                  int NV) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= NV) return;
+  float s = 0.f;
+  for (int p = 0; p < S; ++p) s += part[(size_t)p * NV + c];
+  dw_r[c] = s;
 }
 
 // dq/dk of a shared q/k head = sum over its heads, in increasing head index.
@@ -463,6 +489,28 @@ hipError_t generic_fwd(const FwdArgs &a, hipStream_t s) {
 
 hipError_t generic_bwd(const BwdArgs &a, hipStream_t s) {
   return a.io == 0 ? run_bwd<float>(a, s) : run_bwd<__hip_bfloat16>(a, s);
+}
+
+size_t residual_dw_r_scratch_bytes(int N, int V) {
+  return align256((size_t)kDwrStages * N * V * sizeof(float));
+}
+
+hipError_t residual_dw_r(const BwdArgs &a, hipStream_t s) {
+  const int NV = a.N * a.V;
+  const size_t BT = (size_t)a.B * a.T;
+  const int S = BT < (size_t)kDwrStages ? (int)BT : kDwrStages;
+  if (S > 0) {
+    if (a.io == 0)
+      hipLaunchKernelGGL(dwr_stage1_kernel<float>, dim3(S), dim3(256), 0, s, (const float *)a.dy,
+                         (const float *)a.v, a.dwr_ws, BT, NV);
+    else
+      hipLaunchKernelGGL(dwr_stage1_kernel<__hip_bfloat16>, dim3(S), dim3(256), 0, s,
+                         (const __hip_bfloat16 *)a.dy, (const __hip_bfloat16 *)a.v, a.dwr_ws, BT,
+                         NV);
+  }
+  hipLaunchKernelGGL(dwr_stage2_kernel, dim3((NV + 255) / 256), dim3(256), 0, s,
+                     (const float *)a.dwr_ws, a.dw_r, S, NV);
+  return hipGetLastError();
 }
 
 }  // namespace m2rnn

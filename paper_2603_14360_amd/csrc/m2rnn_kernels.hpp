@@ -17,6 +17,7 @@ struct FwdArgs {
   float *HT, *ckpt;  // ckpt may be null (inference)
   int write_y;       // 0: checkpoint-only pass (the backward's pass 1)
   char *ws;          // workspace base (may be null when nothing is needed)
+  const void *w_r;   // [N,V] io dtype: y_t += w_r (.) v_t; null = no residual
 };
 
 struct BwdArgs {
@@ -26,6 +27,10 @@ struct BwdArgs {
   void *dq, *dk, *dv;
   float *df, *dW, *dH0;
   char *ws;
+  const void *w_r;   // residual weight (dv_t += w_r (.) dy_t); null = none
+  float *dw_r;       // [N,V] fp32 out, with w_r
+  float *dwr_ws;     // scratch of residual_dw_r_scratch_bytes() for dw_r
+  float clip;        // > 0: clamp of the carried state gradient; <= 0: off
 };
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -37,6 +42,10 @@ int generic_max_chunk(int K, int V);
 size_t generic_workspace_bytes(int B, int T, int N, int Nqk, int K, int V, int C, int bwd);
 hipError_t generic_fwd(const FwdArgs &a, hipStream_t s);
 hipError_t generic_bwd(const BwdArgs &a, hipStream_t s);
+
+// dw_r[n][j] = sum over b, t of dy (.) v in a fixed order (two stages through `scratch`)
+size_t residual_dw_r_scratch_bytes(int N, int V);
+hipError_t residual_dw_r(const BwdArgs &a, hipStream_t s);
 
 // ---- matrix-core path (bf16 io, fp16 MFMA operands, fp32 state) ----
 bool mfma_supported(int K, int V);

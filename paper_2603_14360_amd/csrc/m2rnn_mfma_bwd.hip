@@ -99,7 +99,10 @@ struct OvLds {
   static_assert(!OK || BYTES <= kLdsLimit, "LDS overflow");
 };
 
-template <typename TL>
+// CLIP: the gradient handed from step t to step t - 1 is clamped element-wise to
+// [-a.clip, a.clip] as soon as it is formed (the paper's per-step clipping of the state
+// gradient); a separate instantiation, so the exact-gradient kernel pays nothing for it.
+template <typename TL, bool CLIP>
 __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdArgs a, BwdWs ws) {
   constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS, KS = TL::KS,
                 LDH = TL::LDH, WAVES = TL::WAVES;
@@ -521,6 +524,11 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       settle(d);
 #pragma unroll
       for (int r = 0; r < 4; ++r) carry[r] = fmaf(fprev, G[r], d[r]);
+      if constexpr (CLIP) {
+        const float cb = a.clip * sc;  // the sweep works on sc * gradient
+#pragma unroll
+        for (int r = 0; r < 4; ++r) carry[r] = __builtin_amdgcn_fmed3f(carry[r], -cb, cb);
+      }
       if (ct < KS) {
         // v_s in column sp of the B operand only: the other lanes read zeros
         const FragT bf = lds_ld<FragT>(jlB == sp ? bV + (L::VH_ + sp * V * 2) : bZero + L::ZERO_, 0);
@@ -652,9 +660,13 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
           const int sc = 4 * ig + r;
           if (sc < len) {
             const size_t off = (((size_t)b * T + t0 + sc) * N + n) * V + col0 + jl;
-            if constexpr (TL::P == 1)
-              ((bf16_raw *)a.dv)[off] = f32_to_bf16(d[r]);
-            else
+            if constexpr (TL::P == 1) {
+              float x = d[r];
+              if (a.w_r)  // y_t holds w_r (.) v_t as well
+                x = fmaf(bf16_to_f32(((const bf16_raw *)a.w_r)[n * V + col0 + jl]),
+                         bf16_to_f32(dyg[off]), x);
+              ((bf16_raw *)a.dv)[off] = f32_to_bf16(x);
+            } else
               ws.dvp[(size_t)part * a.B * T * N * V + off] = d[r];
           }
         }
@@ -676,16 +688,20 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   }
 }
 
-// dv = bf16(sum of its P parts) when the state is split over workgroups;
-// df = sum of its per-wave partials.  Fixed (increasing) order in both.
+// dv = bf16(sum of its P parts [+ w_r (.) dy for the residual of the y equation]) when the
+// state is split over workgroups; df = sum of its per-wave partials.  Fixed (increasing)
+// order in both.  NV = N * V, the period of w_r along the flat index.
 __global__ void bwd_parts_sum_kernel(const float *__restrict__ dvp, bf16_raw *__restrict__ dv,
                                      size_t n_dv, int P, const float *__restrict__ dfp,
-                                     float *__restrict__ df, size_t n_df, int NP) {
+                                     float *__restrict__ df, size_t n_df, int NP,
+                                     const bf16_raw *__restrict__ w_r,
+                                     const bf16_raw *__restrict__ dy, int NV) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   if (P > 1) {
     for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n_dv; e += stride) {
       float s = dvp[e];
       for (int p = 1; p < P; ++p) s += dvp[(size_t)p * n_dv + e];
+      if (w_r) s = fmaf(bf16_to_f32(w_r[e % (size_t)NV]), bf16_to_f32(dy[e]), s);
       dv[e] = f32_to_bf16(s);
     }
   }
@@ -767,18 +783,20 @@ hipError_t launch_bwd(const BwdArgs &a, hipStream_t s) {
   hipError_t e;
   if (units > 0) {
     if (a.C > OvLds<TL>::CMAX) return hipErrorInvalidValue;
-    e = hipFuncSetAttribute((const void *)mfma_bwd_overlap_kernel<TL>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, OvLds<TL>::BYTES);
+    auto *kern = a.clip > 0.f ? mfma_bwd_overlap_kernel<TL, true> : mfma_bwd_overlap_kernel<TL, false>;
+    e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            OvLds<TL>::BYTES);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(mfma_bwd_overlap_kernel<TL>, dim3(grid_blocks(units, TL::P)),
-                       dim3(2 * TL::THREADS), OvLds<TL>::BYTES, s, a, ws);
+    hipLaunchKernelGGL(kern, dim3(grid_blocks(units, TL::P)), dim3(2 * TL::THREADS),
+                       OvLds<TL>::BYTES, s, a, ws);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (a.T > 0) {
       {
         const size_t n_dv = (size_t)a.B * a.T * a.N * a.V, n_df = (size_t)a.B * a.T * a.N;
         hipLaunchKernelGGL(bwd_parts_sum_kernel, dim3(grid_for(TL::P > 1 ? n_dv : n_df, 256)),
                            dim3(256), 0, s, (const float *)ws.dvp, (bf16_raw *)a.dv, n_dv, TL::P,
-                           (const float *)ws.dfp, a.df, n_df, TL::P * TL::WAVES);
+                           (const float *)ws.dfp, a.df, n_df, TL::P * TL::WAVES,
+                           (const bf16_raw *)a.w_r, (const bf16_raw *)a.dy, a.N * a.V);
       }
       if (shared) {
         const size_t total = (size_t)a.B * a.T * a.Nqk * a.K;

@@ -232,6 +232,14 @@ __global__ void __launch_bounds__(TL::THREADS)
       ys *= kInvC;
       const size_t yoff = (((size_t)b * T + t0 + jl) * N + n) * V + col0 + 4 * ig;
       if constexpr (TL::P == 1) {
+        if (a.w_r) {  // residual w_r (.) v_t of the y equation
+          const uint2 wv = *(const uint2 *)&((const bf16_raw *)a.w_r)[n * V + col0 + 4 * ig];
+          const uint2 vv = *(const uint2 *)&vg[yoff];
+          ys[0] = fmaf(bf16_to_f32(wv.x & 0xFFFFu), bf16_to_f32(vv.x & 0xFFFFu), ys[0]);
+          ys[1] = fmaf(bf16_to_f32(wv.x >> 16), bf16_to_f32(vv.x >> 16), ys[1]);
+          ys[2] = fmaf(bf16_to_f32(wv.y & 0xFFFFu), bf16_to_f32(vv.y & 0xFFFFu), ys[2]);
+          ys[3] = fmaf(bf16_to_f32(wv.y >> 16), bf16_to_f32(vv.y >> 16), ys[3]);
+        }
         uint2 p2;
         p2.x = (uint32_t)f32_to_bf16(ys[0]) | ((uint32_t)f32_to_bf16(ys[1]) << 16);
         p2.y = (uint32_t)f32_to_bf16(ys[2]) | ((uint32_t)f32_to_bf16(ys[3]) << 16);
@@ -292,13 +300,23 @@ __global__ void __launch_bounds__(TL::THREADS)
     for (int r = 0; r < 4; ++r) a.HT[st_off + (size_t)r * V] = h[r] * kInvC;
 }
 
-// y = bf16( sum over parts, in increasing part order )
+// y = bf16( sum over parts, in increasing part order [+ w_r (.) v, the residual of the y
+// equation, when w_r is given] ); NV = N * V, the period of w_r along the flat index
 __global__ void y_parts_sum_kernel(const float *__restrict__ part, bf16_raw *__restrict__ y,
-                                   size_t total, int P) {
+                                   size_t total, int P, const bf16_raw *__restrict__ w_r,
+                                   const bf16_raw *__restrict__ v, int NV) {
   for (size_t e = (blockIdx.x * (size_t)blockDim.x + threadIdx.x) * 4; e < total;
        e += (size_t)gridDim.x * blockDim.x * 4) {
     f4_t s = *(const f4_t *)&part[e];
     for (int p = 1; p < P; ++p) s += *(const f4_t *)&part[(size_t)p * total + e];
+    if (w_r) {
+      const uint2 wv = *(const uint2 *)&w_r[e % (size_t)NV];
+      const uint2 vv = *(const uint2 *)&v[e];
+      s[0] = fmaf(bf16_to_f32(wv.x & 0xFFFFu), bf16_to_f32(vv.x & 0xFFFFu), s[0]);
+      s[1] = fmaf(bf16_to_f32(wv.x >> 16), bf16_to_f32(vv.x >> 16), s[1]);
+      s[2] = fmaf(bf16_to_f32(wv.y & 0xFFFFu), bf16_to_f32(vv.y & 0xFFFFu), s[2]);
+      s[3] = fmaf(bf16_to_f32(wv.y >> 16), bf16_to_f32(vv.y >> 16), s[3]);
+    }
     uint2 pk;
     pk.x = (uint32_t)f32_to_bf16(s[0]) | ((uint32_t)f32_to_bf16(s[1]) << 16);
     pk.y = (uint32_t)f32_to_bf16(s[2]) | ((uint32_t)f32_to_bf16(s[3]) << 16);
@@ -324,20 +342,14 @@ hipError_t launch_fwd(const FwdArgs &a, hipStream_t s) {
     size_t blocks = (total / 4 + 255) / 256;
     if (blocks > 8192) blocks = 8192;
     hipLaunchKernelGGL(y_parts_sum_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                       (const float *)ypart, (bf16_raw *)a.y, total, TL::P);
+                       (const float *)ypart, (bf16_raw *)a.y, total, TL::P,
+                       (const bf16_raw *)a.w_r, (const bf16_raw *)a.v, a.N * a.V);
     e = hipGetLastError();
   }
   return e;
 }
 
 }  // namespace
-
-void y_parts_sum_launch(const float *part, void *y, size_t total, int P, hipStream_t s) {
-  size_t blocks = (total / 4 + 255) / 256;
-  if (blocks > 8192) blocks = 8192;
-  hipLaunchKernelGGL(y_parts_sum_kernel, dim3((unsigned)blocks), dim3(256), 0, s, part,
-                     (bf16_raw *)y, total, P);
-}
 
 // Row blocks per workgroup for a shape: the largest tile that still gives the
 // chip at least one workgroup per CU, else the smallest tile there is.

@@ -294,10 +294,19 @@ __global__ void __launch_bounds__(RW::THREADS) rowwave_fwd_kernel(FwdArgs a) {
 #pragma unroll
         for (int w = 1; w < NW; ++w) ys += *(const f4_t *)&yacc[((sb * NW + w) * TB + s) * V + j];
         ys *= kInvC;
+        const size_t yoff = (((size_t)b * T + t0 + s) * N + n) * V + j;
+        if (a.w_r) {  // residual w_r (.) v_t of the y equation
+          const uint2 wv = *(const uint2 *)&((const bf16_raw *)a.w_r)[n * V + j];
+          const uint2 vv = *(const uint2 *)&((const bf16_raw *)a.v)[yoff];
+          ys[0] = fmaf(bf16_to_f32(wv.x & 0xFFFFu), bf16_to_f32(vv.x & 0xFFFFu), ys[0]);
+          ys[1] = fmaf(bf16_to_f32(wv.x >> 16), bf16_to_f32(vv.x >> 16), ys[1]);
+          ys[2] = fmaf(bf16_to_f32(wv.y & 0xFFFFu), bf16_to_f32(vv.y & 0xFFFFu), ys[2]);
+          ys[3] = fmaf(bf16_to_f32(wv.y >> 16), bf16_to_f32(vv.y >> 16), ys[3]);
+        }
         uint2 p2;
         p2.x = (uint32_t)f32_to_bf16(ys[0]) | ((uint32_t)f32_to_bf16(ys[1]) << 16);
         p2.y = (uint32_t)f32_to_bf16(ys[2]) | ((uint32_t)f32_to_bf16(ys[3]) << 16);
-        *(uint2 *)&yg[(((size_t)b * T + t0 + s) * N + n) * V + j] = p2;
+        *(uint2 *)&yg[yoff] = p2;
       }
     }
   }

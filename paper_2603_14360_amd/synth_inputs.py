@@ -120,6 +120,14 @@ def make_inputs(wl, T=None, B=None, N=None):
     return out
 
 
+def make_residual_weight(wl, N=None):
+    """w_r [N,V]: weights of the residual term w_r (.) v_t, N(0,1), from a generator stream
+    of its own (so that the tensors of make_inputs do not change), rounded to the io dtype."""
+    N = wl.N if N is None else N
+    rng = np.random.default_rng([wl.seed, 7919])
+    return _store(rng.standard_normal((N, wl.V)), wl.io)
+
+
 def select_heads(inp, heads):
     """Restrict workload tensors to a list of heads; the recurrences of
     different heads are independent, so the oracle can be run on the selection

@@ -28,31 +28,37 @@ def to_np(x):
     return x.detach().to("cpu").float().numpy().astype(np.float64)
 
 
-def run_gpu(inp, io, chunk=0, backward=True, use_ckpt=True):
-    """Returns dict of float64 numpy outputs from the HIP library."""
+def run_gpu(inp, io, chunk=0, backward=True, use_ckpt=True, grad_clip=0.0):
+    """Returns dict of float64 numpy outputs from the HIP library.  An input set with a
+    "w_r" entry runs with the residual (and returns dw_r)."""
     import torch
     B, T, Nqk, K = inp["q"].shape
     N, V = inp["v"].shape[2], inp["v"].shape[3]
     dev = to_device(inp, io)
     scan = mb.Scan(B, T, N, K, V, io, Nqk=Nqk, chunk=chunk, backward=backward)
-    y, HT = scan.fwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"])
+    w_r = None
+    if inp.get("w_r") is not None:
+        w_r = torch.from_numpy(np.ascontiguousarray(inp["w_r"], dtype=np.float32)).to("cuda").to(
+            torch.bfloat16 if io == "bf16" else torch.float32)
+    y, HT = scan.fwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"], w_r=w_r)
     out = {"y": to_np(y), "HT": to_np(HT)}
     if backward:
         g = scan.bwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"], dev["dy"],
-                     dev["dHT"], use_ckpt=use_ckpt)
-        for name, x in zip(GRAD_NAMES, g):
+                     dev["dHT"], use_ckpt=use_ckpt, w_r=w_r, grad_clip=grad_clip)
+        for name, x in zip(GRAD_NAMES + ("dw_r",), g):
             out[name] = to_np(x)
     torch.cuda.synchronize()
     return out
 
 
-def run_oracle(inp, backward=True):
+def run_oracle(inp, backward=True, grad_clip=0.0):
     args = [inp[n] for n in ("q", "k", "v", "f", "W")]
-    y, HT = oracle.fwd(*args, inp.get("H0"))
+    y, HT = oracle.fwd(*args, inp.get("H0"), w_r=inp.get("w_r"))
     out = {"y": y, "HT": HT}
     if backward:
-        g = oracle.bwd(*args, inp.get("H0"), inp["dy"], inp.get("dHT"))
-        out.update(dict(zip(GRAD_NAMES, g)))
+        g = oracle.bwd(*args, inp.get("H0"), inp["dy"], inp.get("dHT"), w_r=inp.get("w_r"),
+                       clip=grad_clip)
+        out.update(dict(zip(GRAD_NAMES + ("dw_r",), g)))
     return out
 
 
