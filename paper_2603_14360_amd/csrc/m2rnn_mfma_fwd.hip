@@ -2,9 +2,17 @@
 // tiled variant: a 16-row block of one (b, n) state is spread over V/16 waves.
 //
 // Per workgroup: RB row blocks (16 rows each) of one state, all V columns, for
-// all T steps.  Per step and wavefront (one 16 x 16 tile):
-//   R  read the row block's previous state from LDS as the MFMA A operand and
-//      run the contraction S' = c (H W); W fragments stay in registers.
+// all T steps.  A wavefront owns one 16 x 16 tile; lane l holds row l % 16 and
+// the four columns 4 (l / 16) + r of it.  The contraction is computed
+// transposed, (H W)^T = W^T H^T: W^T is the MFMA A operand (fragments stay in
+// registers) and the state tile is the B operand, whose register layout (lane =
+// row of H, registers = contraction index) is exactly the layout of the MFMA
+// result.  A wave's own tile therefore goes from one step's result to the next
+// step's operand without leaving its registers, and the other V/16 - 1 tiles of
+// the row block are exchanged through LDS as ready-made fragments: one 16-byte
+// write and V/16 - 1 16-byte reads per lane and step, free of bank conflicts.
+// Per step:
+//   R  read the other tiles' fragments and run the contraction S' = c (H W).
 //      The state is exchanged as an fp16 pair (hi, lo) per element, hi + lo
 //      = H' to ~21 bits: the backward through this recurrence amplifies
 //      forward-trajectory errors by orders of magnitude at T = 4096, so a
@@ -12,12 +20,16 @@
 //      k-slots of the MFMA and the W fragment repeats each row of W twice.
 //   E  in registers, fp32:  s' = S' + (c k_i) v_j ; e = 2^{s'} ; r = 1/(1+e) ;
 //      H' <- f H' + c(1-f) - 2c(1-f) r        ( = c [f H + (1-f) tanh(s)] )
-//      split H' into (hi, lo), write the pair back to LDS; one barrier.
-//   Y  readout without leaving the step loop: one 16x16x16 MFMA with A = hi of
-//      the tile (k = rows) and B = q placed in column (t mod 16) only.  The
-//      accumulator is kept for 16 steps, so column s of it collects
-//      c sum_i q_i H[i][j] of step s; nothing is read back per step.  Every 16
-//      steps the row blocks are summed through LDS and 16 rows of y are stored.
+//      split H' into (hi, lo), write the fragment to LDS, start the next step's
+//      contraction with the own tile; one barrier.
+//   Y  readout without leaving the step loop.  It contracts over the rows of H,
+//      which are spread over lanes here, so the tile is first transposed by an
+//      MFMA with an identity operand (exact), then one 16x16x16 MFMA with
+//      A = hi of the transposed tile (k = rows) and B = q placed in column
+//      (t mod 16) only.  The accumulator is kept for 16 steps, so column s of
+//      it collects c sum_i q_i H[i][j] of step s; nothing is read back per step.
+//      Every 16 steps the row blocks are summed through LDS and 16 rows of y
+//      are stored.
 // q, k, v, f for 16 steps at a time are staged through LDS; the next block's
 // global loads are in flight while the current block is computed.
 #include "m2rnn_kernels.hpp"
@@ -30,7 +42,7 @@ constexpr int TB = 16;  // steps per staging / readout block (= MFMA N)
 
 template <typename TL>
 struct FwdSmem {
-  alignas(16) _Float16 Hx[2][TL::ROWS][TL::LDH2];  // (hi, lo) state exchange, padded rows
+  alignas(16) u4_t Hx[2][TL::RB][TL::CT][64];      // (hi, lo) state fragments, one per tile and lane
   alignas(16) float kS[2][TB][TL::ROWS];           // c * k
   alignas(16) _Float16 qS[2][TB][TL::ROWS];
   alignas(16) float vS[2][TB][TL::V];
@@ -67,37 +79,53 @@ __global__ void __launch_bounds__(TL::THREADS)
   const bf16_raw *__restrict__ vg = (const bf16_raw *)a.v;
   const float *__restrict__ fg = a.f;
 
-  // ---- W fragments (B operand).  k-slots 2e, 2e+1 of MFMA m both hold
-  //      W[16 m + 4 ig + e][col0 + jl]: they meet the (hi, lo) pair of that element.
+  // ---- W^T fragments (A operand), in the order the source tiles are used: d = 0 is the
+  //      wave's own tile, d > 0 the tile (ct + d) mod CT.  Lane (jl, ig) holds output column
+  //      col0 + jl; k-slots 2e, 2e+1 of fragment d both hold W[16 m_d + 4 ig + e][col0 + jl]:
+  //      they meet the (hi, lo) pair of that element of the state.
   h8_t wf[CT];
   {
     const bf16_raw *Wn = (const bf16_raw *)a.W + (size_t)n * V * V;
 #pragma unroll
-    for (int m = 0; m < CT; ++m)
+    for (int d = 0; d < CT; ++d) {
+      const int m = (ct + d) % CT;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int c = 16 * m + 4 * ig + e;
         const _Float16 w = (_Float16)bf16_to_f32(Wn[(size_t)c * V + col0 + jl]);
-        wf[m][2 * e] = w;
-        wf[m][2 * e + 1] = w;
+        wf[d][2 * e] = w;
+        wf[d][2 * e + 1] = w;
       }
+    }
   }
 
-  // ---- state tile, scaled by c
-  const size_t st_off = (size_t)unit * K * V + (size_t)(row_base + rowb + 4 * ig) * V + col0 + jl;
+  // ---- state tile, scaled by c: row rowb + jl, columns col0 + 4 ig + r
+  const size_t st_off = (size_t)unit * K * V + (size_t)(row_base + rowb + jl) * V + col0 + 4 * ig;
   float h[4];
+  {
+    const f4_t h0 = a.H0 ? *(const f4_t *)&a.H0[st_off] : f4_t{0.f, 0.f, 0.f, 0.f};
+    if (T == 0) {
+      if (a.HT) *(f4_t *)&a.HT[st_off] = h0;
+      return;
+    }
 #pragma unroll
-  for (int r = 0; r < 4; ++r) h[r] = a.H0 ? kC * a.H0[st_off + (size_t)r * V] : 0.f;
-  if (T == 0) {
-    if (a.HT)
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        a.HT[st_off + (size_t)r * V] = a.H0 ? a.H0[st_off + (size_t)r * V] : 0.f;
-    return;
+    for (int r = 0; r < 4; ++r) h[r] = kC * h0[r];
   }
+  // the own tile as the next contraction's B fragment, and that contraction started with it
+  const f4_t zero4 = {0.f, 0.f, 0.f, 0.f};
+  u4_t own;
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
-    *(uint32_t *)&sm.Hx[0][rowb + 4 * ig + r][2 * (col0 + jl)] = split_hi_lo(h[r]);
+  for (int r = 0; r < 4; ++r) own[r] = split_hi_lo(h[r]);
+  sm.Hx[0][rb][ct][lane] = own;
+  f4_t acc_own = mfma_k32(wf[0], __builtin_bit_cast(h8_t, own), zero4);
+  // LDS byte offsets of the other tiles' fragments (exchange buffer 0)
+  int hx_off[CT];
+#pragma unroll
+  for (int d = 0; d < CT; ++d) hx_off[d] = ((rb * CT + (ct + d) % CT) * 64 + lane) * 16;
+  // identity operand of the transposing MFMA: B[k = 4 ig + r][n = jl] = (k == n)
+  h4_t ident;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) ident[r] = (_Float16)((4 * ig + r == jl) ? 1.f : 0.f);
 
   // ---- staging of q, k, v, f (TB steps per block)
   bf16_raw rq[NQ], rk[NQ], rv[NV];
@@ -170,53 +198,60 @@ __global__ void __launch_bounds__(TL::THREADS)
   // instruction every ~5 cycles at best: loop counters, address arithmetic and branches
   // per step cost as much as the arithmetic).
   struct StepRegs {
-    h8_t af[CT];
-    float f, gp, m2g, vj;
-    f4_t k4, acc;
+    h8_t hf[CT];  // [0] unused: the own tile's product is in acc_own already
+    float f, gp, m2g, kk;
+    f4_t v4, acc;
     h4_t qf;
   };
   auto ckpt_store = [&](int t) __attribute__((always_inline)) {
     if (a.ckpt && t == next_ck) {  // state before step t
       float *dst = a.ckpt + ((size_t)unit * nck + ck_idx) * K * V +
-                   (size_t)(row_base + rowb + 4 * ig) * V + col0 + jl;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) dst[(size_t)r * V] = h[r] * kInvC;
+                   (size_t)(row_base + rowb + jl) * V + col0 + 4 * ig;
+      *(f4_t *)dst = f4_t{h[0], h[1], h[2], h[3]} * kInvC;
       next_ck += a.C;
       ++ck_idx;
     }
   };
-  // R: operand fetch from exchange buffer `buf`, this step's vectors, contraction
-  auto step_R = [&](StepRegs &x, int s, int sb, int buf) __attribute__((always_inline)) {
+  lchar *const hx = (lchar *)&sm.Hx[0][0][0][0];
+  constexpr int HXBUF = RB * CT * 64 * 16;  // bytes of one exchange buffer
+  // L: the other tiles' fragments from exchange buffer `buf` and this step's vectors.
+  //    Issued right after the barrier that completes the buffer, ahead of the previous
+  //    step's readout, so that the readout runs while the fragments are on their way.
+  auto step_L = [&](StepRegs &x, int s, int sb, int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int m = 0; m < CT; ++m)
-      x.af[m] = *(const h8_t *)&sm.Hx[buf][rowb + jl][2 * (16 * m + 4 * ig)];
+    for (int d = 1; d < CT; ++d) x.hf[d] = lds_ld<h8_t>(hx + hx_off[d], buf * HXBUF);
     x.f = sm.fS[sb][s][0];
     x.gp = sm.fS[sb][s][1];
     x.m2g = sm.fS[sb][s][2];
-    x.k4 = *(const f4_t *)&sm.kS[sb][s][rowb + 4 * ig];
-    x.vj = sm.vS[sb][s][col0 + jl];
+    x.kk = sm.kS[sb][s][rowb + jl];
+    x.v4 = *(const f4_t *)&sm.vS[sb][s][col0 + 4 * ig];
     if constexpr (DO_Y) x.qf = *(const h4_t *)&sm.qS[sb][s][rowb + 4 * ig];
-    x.acc = f4_t{0.f, 0.f, 0.f, 0.f};
+  };
+  // R: the contraction (the own tile's product was started in the previous step's E)
+  auto step_R = [&](StepRegs &x) __attribute__((always_inline)) {
+    x.acc = acc_own;
 #pragma unroll
-    for (int m = 0; m < CT; ++m) x.acc = mfma_k32(x.af[m], wf[m], x.acc);
+    for (int d = 1; d < CT; ++d) x.acc = mfma_k32(wf[d], x.hf[d], x.acc);
     settle(x.acc);
   };
-  // E: tanh, gate, split, write back into exchange buffer `buf`
+  // E: tanh, gate, split, fragment into exchange buffer `buf`, own-tile product of the next step
   auto step_E = [&](const StepRegs &x, uint32_t (&pk)[4], int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const float t1 = fmaf(x.f, h[r], x.gp);
-      const float sp = fmaf(x.k4[r], x.vj, x.acc[r]);
+      const float sp = fmaf(x.kk, x.v4[r], x.acc[r]);
       const float e = __builtin_amdgcn_exp2f(sp);
       const float rr = __builtin_amdgcn_rcpf(1.f + e);
       h[r] = fmaf(x.m2g, rr, t1);
       pk[r] = split_hi_lo(h[r]);
     }
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-      *(uint32_t *)&sm.Hx[buf][rowb + 4 * ig + r][2 * (col0 + jl)] = pk[r];
+    const u4_t fr = {pk[0], pk[1], pk[2], pk[3]};
+    if constexpr (CT > 1) lds_st<u4_t>(hx + hx_off[0], buf * HXBUF, fr);
+    acc_own = mfma_k32(wf[0], __builtin_bit_cast(h8_t, fr), zero4);
   };
-  // Y: readout on the matrix core.  A[m = j][k = i] = hi(H'[i][j]) of this tile;
+  // Y: readout on the matrix core.  The tile's hi parts are the A operand [m = i][k = j] as
+  //    they stand; times the identity gives them back with rows in registers and columns in
+  //    lanes (exact: products with 1 and 0).  Then A[m = j][k = i] = hi(H'[i][j]);
   //    B[k = i][n] = q_i for n == s, else 0: column s of yacc collects step s.
   auto step_Y = [&](const StepRegs &x, const uint32_t (&pk)[4], int s, f4_t &yacc)
       __attribute__((always_inline)) {
@@ -224,7 +259,9 @@ __global__ void __launch_bounds__(TL::THREADS)
     uint2 hv;
     hv.x = __builtin_amdgcn_perm(pk[1], pk[0], 0x05040100u);
     hv.y = __builtin_amdgcn_perm(pk[3], pk[2], 0x05040100u);
-    yacc = mfma_k16(__builtin_bit_cast(h4_t, hv), qf, yacc);
+    const f4_t tr = mfma_k16(__builtin_bit_cast(h4_t, hv), ident, zero4);
+    const h4_t ht = {(_Float16)tr[0], (_Float16)tr[1], (_Float16)tr[2], (_Float16)tr[3]};
+    yacc = mfma_k16(ht, qf, yacc);
   };
   auto y_store = [&](f4_t ys, int t0, int len) __attribute__((always_inline)) {
     // lane (ig, jl) holds columns col0 + 4 ig + r of step t0 + jl
@@ -262,24 +299,28 @@ __global__ void __launch_bounds__(TL::THREADS)
       const bool more = blk + 1 < nblk;
       if (more) stage_load(t0 + TB);
       f4_t yacc = {0.f, 0.f, 0.f, 0.f};  // D[m = j][n = s] = c * y partial of step t0 + s
-      auto step = [&](int s) __attribute__((always_inline)) {
-        StepRegs x;
+      StepRegs nx;  // operands of the coming step
+      step_L(nx, 0, sb, 0);
+      auto step = [&](int s, bool last) __attribute__((always_inline)) {
+        StepRegs x = nx;
         ckpt_store(t0 + s);
-        step_R(x, s, sb, s & 1);  // every block but the last has 16 steps: parity of s
+        step_R(x);
         if (s == TB / 2 && more) stage_store(sb ^ 1);  // next block's vectors have landed
         uint32_t pk[4];
-        step_E(x, pk, (s & 1) ^ 1);
+        step_E(x, pk, (s & 1) ^ 1);  // every block but the last has 16 steps: parity of s
         lds_barrier();
-        // after the barrier: the readout MFMA runs while the next step's operands are fetched
+        // after the barrier: fetch the next step's operands, then the readout MFMAs
+        if (!last) step_L(nx, s + 1, sb, (s + 1) & 1);
         if constexpr (DO_Y) step_Y(x, pk, s, yacc);
       };
       if (len == TB) {
 #pragma unroll
-        for (int s = 0; s < TB; ++s) step(s);
+        for (int s = 0; s < TB; ++s) step(s, s == TB - 1);
       } else {
 #pragma nounroll
-        for (int s = 0; s < len; ++s) step(s);
+        for (int s = 0; s < len; ++s) step(s, s == len - 1);
       }
+      settle(yacc);
       if constexpr (DO_Y) {
         // ---- block flush: sum the row blocks, store the block's rows of y
         if constexpr (RB > 1) {
@@ -295,9 +336,7 @@ __global__ void __launch_bounds__(TL::THREADS)
       }
     }
   }
-  if (a.HT)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) a.HT[st_off + (size_t)r * V] = h[r] * kInvC;
+  if (a.HT) *(f4_t *)&a.HT[st_off] = f4_t{h[0], h[1], h[2], h[3]} * kInvC;
 }
 
 // y = bf16( sum over parts, in increasing part order [+ w_r (.) v, the residual of the y
