@@ -112,8 +112,14 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   using FragT = typename Frag<X32>::type;
   using L = OvLds<TL>;
   constexpr int CMAX = L::C_;
-  constexpr int NQ = (CMAX * ROWS + THREADS - 1) / THREADS;
-  constexpr int NV = (CMAX * V + THREADS - 1) / THREADS;
+  // Staging of the per-step vectors: 16-byte items (8 bf16 values of one step), at most one
+  // item per thread and tensor.  The tensors are dealt to different waves of a team where
+  // it has several (thread tid stages item (tid - shift) mod THREADS of a tensor).
+  constexpr int RL = ROWS / 8, VL = V / 8;            // items per step
+  constexpr int QI = CMAX * RL, VI = CMAX * VL;       // items per chunk
+  static_assert(QI <= THREADS && VI <= THREADS, "one staged item per thread and tensor");
+  constexpr int SH_K = 0, SH_V = 64 % THREADS, SH_DY = 192 % THREADS, SH_F = 320 % THREADS,
+                SH_Q = 384 % THREADS;
 
   int unit, part;
   if (!map_block<TL::P>(a.B * a.N, unit, part)) return;
@@ -172,7 +178,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
 #pragma unroll
       for (int e = 0; e < FE; ++e)
         wf[ks][e] = (_Float16)bf16_to_f32(Wn[(size_t)(32 * ks + FE * ig + e) * V + col0 + jl]);
-    bf16_raw rk[NQ], rv[NV], rdy[NV];
+    u4_t rk, rv, rdy;
     float rf = 1.f;
     float hck[4];
     // Global addresses of the staged vectors: a wave-uniform 64-bit base per tensor (batch
@@ -183,60 +189,87 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     const bf16_raw *const dybase = dyg + ((size_t)b * T * N + n) * V;
     const float *const fbase = fg + (size_t)b * T * N + n;
     const uint32_t kstride = (uint32_t)a.Nqk * K, vstride = (uint32_t)N * V;
+    const int ek = (tid - SH_K) & (THREADS - 1), ev = (tid - SH_V) & (THREADS - 1),
+              edy = (tid - SH_DY) & (THREADS - 1), ef = (tid - SH_F) & (THREADS - 1);
+    const bool wave_has_dy = ((wave * 64 - SH_DY) & (THREADS - 1)) < VI;  // wave-uniform
+    const u4_t zero_u4 = {0u, 0u, 0u, 0u};
+    // The loads address memory as uniform base + 32-bit byte offset, and the per-thread part
+    // of the offset is recomputed from the thread index at every call (a few shifts and
+    // adds): kept in registers across the chunk it would be spilled, and a reload from
+    // scratch in front of a load waits for every load issued before it.
     auto stage_load = [&](int ck) {
       const int t0 = ck * C;
       const int len = (T - t0) < C ? (T - t0) : C;
-#pragma unroll
-      for (int m = 0; m < NQ; ++m) {
-        const int idx = tid + m * THREADS;
-        const int s = idx / ROWS, i = idx - s * ROWS;
-        rk[m] = s < len ? kbase[(uint32_t)t0 * kstride + ((uint32_t)s * kstride + i)] : (bf16_raw)0;
+      int tl = tid;
+      asm volatile("" : "+v"(tl));
+      {
+        const int e = (tl - SH_K) & (THREADS - 1), s = e / RL, p = e - s * RL;
+        const uint32_t off = 2u * ((uint32_t)(t0 + s) * kstride + 8u * p);
+        rk = (e < QI && s < len) ? *(const u4_t *)((const char *)kbase + off) : zero_u4;
       }
-#pragma unroll
-      for (int m = 0; m < NV; ++m) {
-        const int idx = tid + m * THREADS;
-        const int s = idx / V, j = idx - s * V;
-        const uint32_t off = (uint32_t)t0 * vstride + ((uint32_t)s * vstride + j);
-        rv[m] = s < len ? vbase[off] : (bf16_raw)0;
-        rdy[m] = s < len ? dybase[off] : (bf16_raw)0;
+      {
+        const int e = (tl - SH_V) & (THREADS - 1), s = e / VL, p = e - s * VL;
+        const uint32_t off = 2u * ((uint32_t)(t0 + s) * vstride + 8u * p);
+        rv = (e < VI && s < len) ? *(const u4_t *)((const char *)vbase + off) : zero_u4;
       }
-      rf = (tid < len) ? fbase[(uint32_t)(t0 + tid) * (uint32_t)N] : 1.f;
-      const float *src = a.ckpt + ((size_t)unit * nck + ck) * K * V + tile_off;
+      {
+        const int e = (tl - SH_DY) & (THREADS - 1), s = e / VL, p = e - s * VL;
+        const uint32_t off = 2u * ((uint32_t)(t0 + s) * vstride + 8u * p);
+        rdy = (e < VI && s < len) ? *(const u4_t *)((const char *)dybase + off) : zero_u4;
+      }
+      {
+        const int e = (tl - SH_F) & (THREADS - 1);
+        rf = (e < len) ? *(const float *)((const char *)fbase + 4u * ((uint32_t)(t0 + e) * (uint32_t)N))
+                       : 1.f;
+      }
+      {
+        const int l = tl & 63;
+        const uint32_t off = 4u * (uint32_t)((row_base + rowb + 4 * (l >> 4)) * V + col0 + (l & 15));
+        const char *src = (const char *)(a.ckpt + ((size_t)unit * nck + ck) * K * V) + off;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) hck[r] = src[(size_t)r * V];
+        for (int r = 0; r < 4; ++r) hck[r] = *(const float *)(src + r * V * 4);
+      }
     };
     auto stage_store = [&]() {
-#pragma unroll
-      for (int m = 0; m < NQ; ++m) asm volatile("" : "+v"(rk[m]));
-#pragma unroll
-      for (int m = 0; m < NV; ++m) asm volatile("" : "+v"(rv[m]), "+v"(rdy[m]));
+      asm volatile("" : "+v"(rk), "+v"(rv), "+v"(rdy));
       asm volatile("" : "+v"(rf), "+v"(hck[0]), "+v"(hck[1]), "+v"(hck[2]), "+v"(hck[3]));
-#pragma unroll
-      for (int m = 0; m < NQ; ++m) {
-        const int idx = tid + m * THREADS;
-        if (idx < CMAX * ROWS) kS[idx] = kC * bf16_to_f32(rk[m]);
+      float x[8];
+      if (ek < QI) {
+        bf16x8_to_f32(rk, x);
+        *(f4_t *)&kS[8 * ek] = f4_t{x[0], x[1], x[2], x[3]} * kC;
+        *(f4_t *)&kS[8 * ek + 4] = f4_t{x[4], x[5], x[6], x[7]} * kC;
       }
-#pragma unroll
-      for (int m = 0; m < NV; ++m) {
-        const int idx = tid + m * THREADS;
+      if (ev < VI) {
+        bf16x8_to_f32(rv, x);
+        *(f4_t *)&vS[8 * ev] = f4_t{x[0], x[1], x[2], x[3]};
+        *(f4_t *)&vS[8 * ev + 4] = f4_t{x[4], x[5], x[6], x[7]};
+      }
+      if (wave_has_dy) {
         // dy_s enters the dq contraction as fp16: each step's row is scaled by a power of two
         // so that its largest entry lands in [2^10, 2^11) (loss-scaled or token-averaged
         // gradients are far outside the fp16 range); column s of dq is scaled back at the end
         // (a row of V = 128 has two halves of 64 columns with a scale each: a dq slice
-        //  covers 32 columns, i.e. lies inside one half)
-        constexpr int GRP = V < 64 ? V : 64;
-        const bool in = idx < CMAX * V;
-        const float dyf = in ? bf16_to_f32(rdy[m]) : 0.f;
-        const int e = ilog2f(fminf(fmaxf(group_max_nonneg<GRP>(fabsf(dyf)), 1e-30f), 1e30f));
-        if (in) {
-          vS[idx] = bf16_to_f32(rv[m]);
-          dyH[idx] = (_Float16)(dyf * pow2i(10 - e));
-          if (idx % GRP == 0) fA[(idx / V) * 4 + 2 + (idx % V) / 64] = pow2i(e - 10);
+        //  covers 32 columns, i.e. lies inside one half).  A row (half row) is held by
+        // GL consecutive lanes, 8 values each.
+        constexpr int GL = (V < 64 ? V : 64) / 8;
+        bf16x8_to_f32(rdy, x);
+        float mx = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mx = fmaxf(mx, fabsf(x[i]));
+        const int e = ilog2f(fminf(fmaxf(group_max_nonneg<GL>(mx), 1e-30f), 1e30f));
+        if (edy < VI) {
+          const float up = pow2i(10 - e);
+          h8_t hv;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) hv[i] = (_Float16)(x[i] * up);
+          *(h8_t *)&dyH[8 * edy] = hv;
+          const int s = edy / VL, p = edy - s * VL;
+          if (p % GL == 0) fA[s * 4 + 2 + (8 * p) / 64] = pow2i(e - 10);
         }
       }
-      if (tid < CMAX) {
-        fA[tid * 4 + 0] = rf;
-        fA[tid * 4 + 1] = kC * (1.f - rf);
+      if (ef < CMAX) {
+        fA[ef * 4 + 0] = rf;
+        fA[ef * 4 + 1] = kC * (1.f - rf);
       }
     };
     // dq of chunk step s_col (= H after that step, times dy of that step): wave ct < KS adds
@@ -270,7 +303,10 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) Hx[cur * ROWS + rowb + 4 * ig + r][col0 + jl] = hp[r];
-        if (ck > 0) stage_load(ck - 1);  // next chunk's vectors travel during this chunk
+        // next chunk's vectors and checkpoint travel during this chunk.  Unconditional (the
+        // last iteration fetches chunk 0 again): a conditional fetch makes the compiler merge
+        // the old and the new register values right here, which waits for the loads.
+        stage_load(ck > 0 ? ck - 1 : 0);
       }
       lds_barrier();  // P
       // one recomputed step; `s` and the exchange buffer parity are compile-time constants
@@ -345,12 +381,17 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         for (int ks = 1; ks < KS; ++ks)
           d += fin[(rb * KS + ks) * 64 + lane] * fA[jl * 4 + 2 + (32 * ks) / 64];
         d *= kInvC;
-        const int t = t0 + jl;
-        if (ws.dqh)
-          *(f4_t *)&ws.dqh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
-        else
-          *(uint2 *)&((bf16_raw *)a.dq)[(((size_t)b * T + t) * a.Nqk + g) * K + row_base + rowb +
-                                        4 * ig] = pack4_bf16(d);
+        // (uniform base + 32-bit byte offset rebuilt from the lane index: see stage_load)
+        int ll = lane;
+        asm volatile("" : "+v"(ll));
+        const uint32_t jl2 = ll & 15, ig2 = ll >> 4;
+        if (ws.dqh) {
+          char *base = (char *)(ws.dqh + (((size_t)b * T + t0) * N + n) * K + row_base + rowb);
+          *(f4_t *)(base + 4u * (jl2 * (uint32_t)(N * K) + 4u * ig2)) = d;
+        } else {
+          char *base = (char *)((bf16_raw *)a.dq + (((size_t)b * T + t0) * a.Nqk + g) * K + row_base + rowb);
+          *(uint2 *)(base + 2u * (jl2 * kstride + 4u * ig2)) = pack4_bf16(d);
+        }
       }
       lds_barrier();  // E3
     }
@@ -384,7 +425,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
                                        // by iteration parity; filled with LDS atomic max
   auto wave_max = [&](float x) { return group_max_nonneg<64>(x); };
 
-  bf16_raw rq[NQ], rk[NQ], rv[NV], rdy[NV];
+  u4_t rq, rk, rv, rdy;
   float rf = 1.f;
   // (addresses as in team A: uniform base + 32-bit element offset)
   const bf16_raw *const qbase = qg + ((size_t)b * T * a.Nqk + g) * K + row_base;
@@ -393,69 +434,91 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   const bf16_raw *const dybase = dyg + ((size_t)b * T * N + n) * V;
   const float *const fbase = fg + (size_t)b * T * N + n;
   const uint32_t kstride = (uint32_t)a.Nqk * K, vstride = (uint32_t)N * V;
-  auto stage_load = [&](int ck) {
+  const int eq = (tid - SH_Q) & (THREADS - 1), ek = (tid - SH_K) & (THREADS - 1),
+            ev = (tid - SH_V) & (THREADS - 1), edy = (tid - SH_DY) & (THREADS - 1),
+            ef = (tid - SH_F) & (THREADS - 1);
+  const bool wave_has_q = ((wave * 64 - SH_Q) & (THREADS - 1)) < QI;    // wave-uniform
+  const bool wave_has_dy = ((wave * 64 - SH_DY) & (THREADS - 1)) < VI;
+  const u4_t zero_u4 = {0u, 0u, 0u, 0u};
+  auto stage_load = [&](int ck) {  // (addresses as in team A)
     const int t0 = ck * C;
     const int len = (T - t0) < C ? (T - t0) : C;
-#pragma unroll
-    for (int m = 0; m < NQ; ++m) {
-      const int idx = tid + m * THREADS;
-      const int s = idx / ROWS, i = idx - s * ROWS;
-      const uint32_t off = (uint32_t)t0 * kstride + ((uint32_t)s * kstride + i);
-      rq[m] = s < len ? qbase[off] : (bf16_raw)0;
-      rk[m] = s < len ? kbase[off] : (bf16_raw)0;
-    }
-#pragma unroll
-    for (int m = 0; m < NV; ++m) {
-      const int idx = tid + m * THREADS;
-      const int s = idx / V, j = idx - s * V;
-      const uint32_t off = (uint32_t)t0 * vstride + ((uint32_t)s * vstride + j);
-      rv[m] = s < len ? vbase[off] : (bf16_raw)0;
-      rdy[m] = s < len ? dybase[off] : (bf16_raw)0;
-    }
-    rf = (tid < len) ? fbase[(uint32_t)(t0 + tid) * (uint32_t)N] : 1.f;
-  };
-  auto stage_store = [&]() {
-#pragma unroll
-    for (int m = 0; m < NQ; ++m) asm volatile("" : "+v"(rq[m]), "+v"(rk[m]));
-#pragma unroll
-    for (int m = 0; m < NV; ++m) asm volatile("" : "+v"(rv[m]), "+v"(rdy[m]));
-    asm volatile("" : "+v"(rf));
-#pragma unroll
-    for (int m = 0; m < NQ; ++m) {
-      const int idx = tid + m * THREADS;
-      if (idx < CMAX * ROWS) {
-        qS[idx] = bf16_to_f32(rq[m]);
-        kH[idx] = (_Float16)bf16_to_f32(rk[m]);
-      }
-    }
-#pragma unroll
-    for (int m = 0; m < NV; ++m) {
-      const int idx = tid + m * THREADS;
-      if (idx < CMAX * V) {
-        dyS[idx] = bf16_to_f32(rdy[m]);
-        vH[idx] = (_Float16)bf16_to_f32(rv[m]);
-      }
+    int tl = tid;
+    asm volatile("" : "+v"(tl));
+    {
+      const int e = (tl - SH_Q) & (THREADS - 1), s = e / RL, p = e - s * RL;
+      const uint32_t off = 2u * ((uint32_t)(t0 + s) * kstride + 8u * p);
+      rq = (e < QI && s < len) ? *(const u4_t *)((const char *)qbase + off) : zero_u4;
     }
     {
-      float mq = 0.f, md = 0.f;
-#pragma unroll
-      for (int m = 0; m < NQ; ++m) mq = fmaxf(mq, fabsf(bf16_to_f32(rq[m])));
-#pragma unroll
-      for (int m = 0; m < NV; ++m) md = fmaxf(md, fabsf(bf16_to_f32(rdy[m])));
-      mq = wave_max(mq);
-      md = wave_max(md);
-      if (lane == 0) {  // (non-negative floats order like their bit patterns)
-        atomicMax(&scl[4 * set_now + 1], __builtin_bit_cast(int, mq));
-        atomicMax(&scl[4 * set_now + 2], __builtin_bit_cast(int, md));
-      }
+      const int e = (tl - SH_K) & (THREADS - 1), s = e / RL, p = e - s * RL;
+      const uint32_t off = 2u * ((uint32_t)(t0 + s) * kstride + 8u * p);
+      rk = (e < QI && s < len) ? *(const u4_t *)((const char *)kbase + off) : zero_u4;
     }
-    if (tid < CMAX) {
+    {
+      const int e = (tl - SH_V) & (THREADS - 1), s = e / VL, p = e - s * VL;
+      const uint32_t off = 2u * ((uint32_t)(t0 + s) * vstride + 8u * p);
+      rv = (e < VI && s < len) ? *(const u4_t *)((const char *)vbase + off) : zero_u4;
+    }
+    {
+      const int e = (tl - SH_DY) & (THREADS - 1), s = e / VL, p = e - s * VL;
+      const uint32_t off = 2u * ((uint32_t)(t0 + s) * vstride + 8u * p);
+      rdy = (e < VI && s < len) ? *(const u4_t *)((const char *)dybase + off) : zero_u4;
+    }
+    {
+      const int e = (tl - SH_F) & (THREADS - 1);
+      rf = (e < len) ? *(const float *)((const char *)fbase + 4u * ((uint32_t)(t0 + e) * (uint32_t)N))
+                     : 1.f;
+    }
+  };
+  auto stage_store = [&]() {
+    asm volatile("" : "+v"(rq), "+v"(rk), "+v"(rv), "+v"(rdy), "+v"(rf));
+    float x[8];
+    if (wave_has_q) {
+      bf16x8_to_f32(rq, x);
+      if (eq < QI) {
+        *(f4_t *)&qS[8 * eq] = f4_t{x[0], x[1], x[2], x[3]};
+        *(f4_t *)&qS[8 * eq + 4] = f4_t{x[4], x[5], x[6], x[7]};
+      }
+      float mq = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) mq = fmaxf(mq, fabsf(x[i]));
+      mq = wave_max(mq);  // (non-negative floats order like their bit patterns)
+      if (lane == 0) atomicMax(&scl[4 * set_now + 1], __builtin_bit_cast(int, mq));
+    }
+    if (ek < QI) {
+      bf16x8_to_f32(rk, x);
+      h8_t hv;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) hv[i] = (_Float16)x[i];
+      *(h8_t *)&kH[8 * ek] = hv;
+    }
+    if (ev < VI) {
+      bf16x8_to_f32(rv, x);
+      h8_t hv;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) hv[i] = (_Float16)x[i];
+      *(h8_t *)&vH[8 * ev] = hv;
+    }
+    if (wave_has_dy) {
+      bf16x8_to_f32(rdy, x);
+      if (edy < VI) {
+        *(f4_t *)&dyS[8 * edy] = f4_t{x[0], x[1], x[2], x[3]};
+        *(f4_t *)&dyS[8 * edy + 4] = f4_t{x[4], x[5], x[6], x[7]};
+      }
+      float md = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) md = fmaxf(md, fabsf(x[i]));
+      md = wave_max(md);
+      if (lane == 0) atomicMax(&scl[4 * set_now + 2], __builtin_bit_cast(int, md));
+    }
+    if (ef < CMAX) {
       const float gm = 1.f - rf;
       const h2_t m2 = {(_Float16)(gm * (-kInvC * kInvC)), (_Float16)(gm * (-kInvC * kInvC))};
       const h2_t g2 = {(_Float16)gm, (_Float16)gm};
-      fB[tid * 4 + 0] = rf;
-      fB[tid * 4 + 1] = __builtin_bit_cast(float, m2);
-      fB[tid * 4 + 2] = __builtin_bit_cast(float, g2);
+      fB[ef * 4 + 0] = rf;
+      fB[ef * 4 + 1] = __builtin_bit_cast(float, m2);
+      fB[ef * 4 + 2] = __builtin_bit_cast(float, g2);
     }
   };
 
@@ -469,7 +532,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     set_now = it & 1;  // maxima that decide this chunk's scale
     if (active) {
       stage_store();
-      if (ck > 0) stage_load(ck - 1);
+      stage_load(ck > 0 ? ck - 1 : 0);  // (unconditional: see team A)
     }
     lds_barrier();  // P: this chunk's stash entries were completed by team A in the previous iteration
     // the other set was read one iteration ago and is filled again from the end of this one
@@ -628,46 +691,56 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     // partials: dk slices behind team A's dq slices in A's exchange buffer, dv in B's own
     f4_t *fink = (f4_t *)(lds + L::HX) + RB * KS * 64;  // [RB][KS][64]
     f4_t *finv = (f4_t *)(lds + L::DX);                 // [WAVES][64]
+    // Store addresses below: wave-uniform 64-bit base + 32-bit byte offset rebuilt from the
+    // lane index on the spot.  Kept in registers over the chunk they would be spilled, and a
+    // reload from scratch in front of a store waits for every store issued before it.
+    int ll = lane;
+    asm volatile("" : "+v"(ll));
+    const uint32_t jl2 = ll & 15, ig2 = ll >> 4;
     if (active) {
       if (ct < KS) fink[(rb * KS + ct) * 64 + lane] = dkacc * isc;
       finv[wave * 64 + lane] = dvacc * isc;
       float x = (dfacc[0] + dfacc[1]) + (dfacc[2] + dfacc[3]);
       x += __shfl_xor(x, 16, 64);
       x += __shfl_xor(x, 32, 64);
-      if (lane < 16 && jl < len)
-        ws.dfp[((size_t)(part * WAVES + wave) * a.B * T + (size_t)b * T + t0 + jl) * N + n] =
-            x * (kInvC * isc);
+      if (ll < 16 && (int)jl2 < len) {
+        char *base = (char *)(ws.dfp + ((size_t)(part * WAVES + wave) * a.B * T + (size_t)b * T + t0) * N + n);
+        *(float *)(base + 4u * (jl2 * (uint32_t)N)) = x * (kInvC * isc);
+      }
     }
     lds_barrier();  // E2
     if (active) {
-      if (ct == 0 && jl < len) {
+      if (ct == 0 && (int)jl2 < len) {
         f4_t d = fink[(rb * KS + 0) * 64 + lane];
 #pragma unroll
         for (int ks = 1; ks < KS; ++ks) d += fink[(rb * KS + ks) * 64 + lane];
-        const int t = t0 + jl;
-        if (ws.dkh)
-          *(f4_t *)&ws.dkh[(((size_t)b * T + t) * N + n) * K + row_base + rowb + 4 * ig] = d;
-        else
-          *(uint2 *)&((bf16_raw *)a.dk)[(((size_t)b * T + t) * a.Nqk + g) * K + row_base + rowb +
-                                        4 * ig] = pack4_bf16(d);
+        if (ws.dkh) {
+          char *base = (char *)(ws.dkh + (((size_t)b * T + t0) * N + n) * K + row_base + rowb);
+          *(f4_t *)(base + 4u * (jl2 * (uint32_t)(N * K) + 4u * ig2)) = d;
+        } else {
+          char *base = (char *)((bf16_raw *)a.dk + (((size_t)b * T + t0) * a.Nqk + g) * K + row_base + rowb);
+          *(uint2 *)(base + 2u * (jl2 * kstride + 4u * ig2)) = pack4_bf16(d);
+        }
       }
       if (rb == 0) {
         f4_t d = finv[(0 * CT + ct) * 64 + lane];
 #pragma unroll
         for (int r2 = 1; r2 < RB; ++r2) d += finv[(r2 * CT + ct) * 64 + lane];
+        const size_t row0 = (((size_t)b * T + t0) * N + n) * V + col0;  // uniform: step t0, column col0
+        const uint32_t eoff = 4u * ig2 * vstride + jl2;                 // element offset of (step 4 ig, column jl)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int sc = 4 * ig + r;
+          const int sc = 4 * (int)ig2 + r;
           if (sc < len) {
-            const size_t off = (((size_t)b * T + t0 + sc) * N + n) * V + col0 + jl;
+            const uint32_t eo = eoff + (uint32_t)r * vstride;
             if constexpr (TL::P == 1) {
               float x = d[r];
               if (a.w_r)  // y_t holds w_r (.) v_t as well
-                x = fmaf(bf16_to_f32(((const bf16_raw *)a.w_r)[n * V + col0 + jl]),
-                         bf16_to_f32(dyg[off]), x);
-              ((bf16_raw *)a.dv)[off] = f32_to_bf16(x);
+                x = fmaf(bf16_to_f32(((const bf16_raw *)a.w_r)[n * V + col0 + (int)jl2]),
+                         bf16_to_f32(*(const bf16_raw *)((const char *)(dyg + row0) + 2u * eo)), x);
+              *(bf16_raw *)((char *)((bf16_raw *)a.dv + row0) + 2u * eo) = f32_to_bf16(x);
             } else
-              ws.dvp[(size_t)part * a.B * T * N * V + off] = d[r];
+              *(float *)((char *)(ws.dvp + (size_t)part * a.B * T * N * V + row0) + 4u * eo) = d[r];
           }
         }
       }

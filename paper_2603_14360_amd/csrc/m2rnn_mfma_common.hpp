@@ -103,18 +103,21 @@ __device__ __forceinline__ f4_t mfma_k16(h4_t a, h4_t b, f4_t c) {
 // that skip the block read the accumulator too early (seen as wrong gradients).
 __device__ __forceinline__ void settle(f4_t &d) { asm volatile("" : "+v"(d)); }
 
-// Maximum of a NON-NEGATIVE float over aligned groups of G = 16, 32 or 64 consecutive lanes
-// (result in every lane of the group), without LDS traffic: four DPP steps inside each row
+// Maximum of a NON-NEGATIVE float over aligned groups of G = 2, 4, 8, 16, 32 or 64 consecutive
+// lanes (result in every lane of the group), without LDS traffic: DPP steps inside each row
 // of 16 lanes, then the rows through scalar registers.  Non-negative floats order like
 // their bit patterns, so the maxima are taken on integers.
 template <int G>
 __device__ __forceinline__ float group_max_nonneg(float x) {
-  static_assert(G == 16 || G == 32 || G == 64, "group size");
+  static_assert(G == 2 || G == 4 || G == 8 || G == 16 || G == 32 || G == 64, "group size");
   int v = __builtin_bit_cast(int, x);
   v = max(v, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
-  v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
-  v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false));  // row_half_mirror
-  v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, false));  // row_mirror
+  if constexpr (G > 2)
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  if constexpr (G > 4)
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  if constexpr (G > 8)
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, false));  // row_mirror
   if constexpr (G > 16) {
     const int r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
     const int r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
@@ -124,6 +127,14 @@ __device__ __forceinline__ float group_max_nonneg(float x) {
       v = (threadIdx.x & 32) ? max(r2, r3) : max(r0, r1);
   }
   return __builtin_bit_cast(float, v);
+}
+// eight bf16 values (one 16-byte load) widened to fp32
+__device__ __forceinline__ void bf16x8_to_f32(const u4_t &w, float (&x)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = __builtin_bit_cast(float, w[i] << 16);
+    x[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xFFFF0000u);
+  }
 }
 // 2^e with e clamped to the normal range
 __device__ __forceinline__ float pow2i(int e) {
