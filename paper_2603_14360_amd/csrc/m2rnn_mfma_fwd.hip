@@ -130,25 +130,31 @@ __global__ void __launch_bounds__(TL::THREADS)
   // ---- staging of q, k, v, f (TB steps per block)
   bf16_raw rq[NQ], rk[NQ], rv[NV];
   float rf = 1.f;
+  // Every thread loads from a valid (clamped) address and nothing is zero-filled: steps past
+  // the end of the sequence are staged but never used.  (A load under a condition needs its
+  // register cleared first, and the wait in front of that write also waits for the stores
+  // in flight.)
   auto stage_load = [&](int t0) {
 #pragma unroll
     for (int m = 0; m < NQ; ++m) {
       const int idx = tid + m * THREADS;
       const int s = idx / ROWS, i = idx - s * ROWS;
-      const bool ok = idx < TB * ROWS && t0 + s < T;
-      const size_t off = (((size_t)b * T + (t0 + s)) * a.Nqk + g) * K + row_base + i;
-      rq[m] = ok ? qg[off] : (bf16_raw)0;
-      rk[m] = ok ? kg[off] : (bf16_raw)0;
+      const int t = (t0 + s) < T ? (t0 + s) : (T - 1);
+      const size_t off = (((size_t)b * T + t) * a.Nqk + g) * K + row_base + i;
+      rq[m] = qg[off];
+      rk[m] = kg[off];
     }
 #pragma unroll
     for (int m = 0; m < NV; ++m) {
       const int idx = tid + m * THREADS;
       const int s = idx / V, j = idx - s * V;
-      const bool ok = idx < TB * V && t0 + s < T;
-      const size_t off = (((size_t)b * T + (t0 + s)) * N + n) * V + j;
-      rv[m] = ok ? vg[off] : (bf16_raw)0;
+      const int t = (t0 + s) < T ? (t0 + s) : (T - 1);
+      rv[m] = vg[(((size_t)b * T + t) * N + n) * V + j];
     }
-    rf = (tid < TB && t0 + tid < T) ? fg[((size_t)b * T + (t0 + tid)) * N + n] : 1.f;
+    {
+      const int t = (t0 + (tid & (TB - 1))) < T ? (t0 + (tid & (TB - 1))) : (T - 1);
+      rf = fg[((size_t)b * T + t) * N + n];
+    }
   };
   auto stage_store = [&](int buf) {
     // keep the conversions here: hoisted to the loads they would wait for the loads at once
@@ -297,7 +303,10 @@ __global__ void __launch_bounds__(TL::THREADS)
       const int len = (T - t0) < TB ? (T - t0) : TB;
       const int sb = blk & 1;
       const bool more = blk + 1 < nblk;
-      if (more) stage_load(t0 + TB);
+      // Unconditional (the last block fetches itself again): a conditional fetch makes the
+      // compiler merge old and new register values at the loop head, and the wait it puts
+      // there also waits for the y and checkpoint stores of the block before.
+      stage_load(more ? t0 + TB : t0);
       f4_t yacc = {0.f, 0.f, 0.f, 0.f};  // D[m = j][n = s] = c * y partial of step t0 + s
       StepRegs nx;  // operands of the coming step
       step_L(nx, 0, sb, 0);
@@ -305,7 +314,10 @@ __global__ void __launch_bounds__(TL::THREADS)
         StepRegs x = nx;
         ckpt_store(t0 + s);
         step_R(x);
-        if (s == TB / 2 && more) stage_store(sb ^ 1);  // next block's vectors have landed
+        // next block's vectors have landed.  (Also when there is no next block: every path
+        // through a block then uses the fetched registers, and the compiler puts no wait for
+        // them -- which would also wait for the stores in flight -- at the head of the next.)
+        if (s == TB / 2) stage_store(sb ^ 1);
         uint32_t pk[4];
         step_E(x, pk, (s & 1) ^ 1);  // every block but the last has 16 steps: parity of s
         lds_barrier();
@@ -319,6 +331,11 @@ __global__ void __launch_bounds__(TL::THREADS)
       } else {
 #pragma nounroll
         for (int s = 0; s < len; ++s) step(s, s == len - 1);
+#pragma unroll
+        for (int m = 0; m < NQ; ++m) asm volatile("" : : "v"(rq[m]), "v"(rk[m]));
+#pragma unroll
+        for (int m = 0; m < NV; ++m) asm volatile("" : : "v"(rv[m]));
+        asm volatile("" : : "v"(rf));
       }
       settle(yacc);
       if constexpr (DO_Y) {
