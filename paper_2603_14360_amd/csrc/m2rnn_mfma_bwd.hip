@@ -303,12 +303,13 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) Hx[cur * ROWS + rowb + 4 * ig + r][col0 + jl] = hp[r];
-        // next chunk's vectors and checkpoint travel during this chunk.  Unconditional (the
-        // last iteration fetches chunk 0 again): a conditional fetch makes the compiler merge
-        // the old and the new register values right here, which waits for the loads.
-        stage_load(ck > 0 ? ck - 1 : 0);
       }
       lds_barrier();  // P
+      // Next chunk's vectors and checkpoint travel during this chunk; issued behind the
+      // barrier, where this team has slack (team B waits for it there).  Unconditional (the
+      // last iterations fetch chunk 0 again): a conditional fetch makes the compiler merge
+      // the old and the new register values right here, which waits for the loads.
+      stage_load(ck > 0 ? ck - 1 : 0);
       // one recomputed step; `s` and the exchange buffer parity are compile-time constants
       // in the unrolled loop below (per-step loop overhead costs as much as the arithmetic)
       auto stepA = [&](int s) __attribute__((always_inline)) {
