@@ -36,6 +36,12 @@
  * form, the f=1 / f=0 gate limits, segment chaining, row independence and
  * permutation symmetries, the |H|<=1 bound, linearity of the backward.
  *
+ * Forget gate (the paper's "Forget Gate" section): with gate parameters alpha, beta
+ * (one each per head) the argument f holds the gate's input x, and the gate value is
+ * f = psi(x) = (1 + e^(x + beta))^(-alpha); the backward then returns the gradient with
+ * respect to x in df, and dalpha, dbeta summed over b and t.  Without them f is the gate
+ * value itself.
+ *
  * Layouts (dense, row-major, host memory, all double):
  *   q, k  [B,T,Nqk,K]   v, y, dy, dv [B,T,N,V]   f, df [B,T,N]
  *   W, dW [N,V,V]       H0, HT, dHT, dH0 [B,N,K,V]     w_r, dw_r [N,V]
@@ -67,6 +73,15 @@ int m2rnn_oracle_num_threads(void) {
 #endif
 }
 
+/* psi(x) = (1 + e^(x + beta))^(-alpha), through log1p for large |x + beta| */
+static double softplus(double u) {
+  return (u > 0.0 ? u : 0.0) + log1p(exp(-fabs(u)));
+}
+static double gate_value(const double *alpha, const double *beta, int n, double x) {
+  if (!alpha) return x;
+  return exp(-alpha[n] * softplus(x + beta[n]));
+}
+
 /* One step of the recurrence for one (b, n): H (K x V) is updated in place.
  * Z, if not NULL, receives tanh(H_prev W + k v^T).  S is K*V scratch. */
 static void step_forward(int K, int V, const double *W, const double *kt,
@@ -89,7 +104,8 @@ static void step_forward(int K, int V, const double *W, const double *kt,
 int m2rnn_oracle_fwd(int B, int T, int N, int Nqk, int K, int V,
                      const double *q, const double *k, const double *v,
                      const double *f, const double *W, const double *H0,
-                     const double *w_r, double *y, double *HT) {
+                     const double *w_r, const double *alpha, const double *beta,
+                     double *y, double *HT) {
   if (B < 0 || T < 0 || N <= 0 || Nqk <= 0 || K <= 0 || V <= 0) return 1;
   if (N % Nqk != 0) return 1;
   const int heads_per_group = N / Nqk;
@@ -113,7 +129,7 @@ int m2rnn_oracle_fwd(int B, int T, int N, int Nqk, int K, int V,
         memset(H, 0, sizeof(double) * K * V);
       for (int t = 0; t < T; ++t) {
         step_forward(K, V, Wn, k + IDX_QK(b, t, g, 0), v + IDX_V(b, t, n, 0),
-                     f[IDX_F(b, t, n)], H, S, NULL);
+                     gate_value(alpha, beta, n, f[IDX_F(b, t, n)]), H, S, NULL);
         const double *qt = q + IDX_QK(b, t, g, 0);
         for (int j = 0; j < V; ++j) {
           double acc = 0.0;
@@ -137,9 +153,10 @@ int m2rnn_oracle_fwd(int B, int T, int N, int Nqk, int K, int V,
 int m2rnn_oracle_bwd(int B, int T, int N, int Nqk, int K, int V,
                      const double *q, const double *k, const double *v,
                      const double *f, const double *W, const double *H0,
-                     const double *w_r, double clip, const double *dy,
-                     const double *dHT, double *dq, double *dk, double *dv,
-                     double *df, double *dW, double *dH0, double *dw_r) {
+                     const double *w_r, double clip, const double *alpha,
+                     const double *beta, const double *dy, const double *dHT,
+                     double *dq, double *dk, double *dv, double *df, double *dW,
+                     double *dH0, double *dw_r, double *dalpha, double *dbeta) {
   if (B < 0 || T < 0 || N <= 0 || Nqk <= 0 || K <= 0 || V <= 0) return 1;
   if (N % Nqk != 0) return 1;
   const int heads_per_group = N / Nqk;
@@ -181,7 +198,8 @@ int m2rnn_oracle_bwd(int B, int T, int N, int Nqk, int K, int V,
         memcpy(Hall + (size_t)(t + 1) * KV, Hall + (size_t)t * KV,
                sizeof(double) * KV);
         step_forward(K, V, Wn, k + IDX_QK(b, t, g, 0), v + IDX_V(b, t, n, 0),
-                     f[IDX_F(b, t, n)], Hall + (size_t)(t + 1) * KV, S, NULL);
+                     gate_value(alpha, beta, n, f[IDX_F(b, t, n)]),
+                     Hall + (size_t)(t + 1) * KV, S, NULL);
       }
       /* gradient carried into the last state */
       if (dHT)
@@ -197,7 +215,7 @@ int m2rnn_oracle_bwd(int B, int T, int N, int Nqk, int K, int V,
         const double *kt = k + IDX_QK(b, t, g, 0);
         const double *vt = v + IDX_V(b, t, n, 0);
         const double *dyt = dy + IDX_V(b, t, n, 0);
-        const double ft = f[IDX_F(b, t, n)];
+        const double ft = gate_value(alpha, beta, n, f[IDX_F(b, t, n)]);
         /* recompute Z_t from the state before the step */
         memcpy(Hp, Hprev, sizeof(double) * KV);
         step_forward(K, V, Wn, kt, vt, ft, Hp, S, Z);
@@ -273,6 +291,26 @@ int m2rnn_oracle_bwd(int B, int T, int N, int Nqk, int K, int V,
       for (int b = 0; b < B; ++b) s += dW_unit[((size_t)b * N + n) * V * V + e];
       dW[(size_t)n * V * V + e] = s;
     }
+  /* through the gate function: df holds dL/d(gate value) so far.
+   * d psi/dx = d psi/dbeta = -alpha psi sigmoid(x + beta);  d psi/dalpha = -psi softplus(x + beta) */
+  if (alpha) {
+    for (int n = 0; n < N; ++n) {
+      double sa = 0.0, sb = 0.0;
+      for (int b = 0; b < B; ++b)
+        for (int t = 0; t < T; ++t) {
+          const double u = f[IDX_F(b, t, n)] + beta[n];
+          const double sp = softplus(u);
+          const double psi = exp(-alpha[n] * sp);
+          const double g = df[IDX_F(b, t, n)];
+          const double dx = -g * alpha[n] * psi / (1.0 + exp(-u));
+          sa += -g * psi * sp;
+          sb += dx;
+          df[IDX_F(b, t, n)] = dx;
+        }
+      dalpha[n] = sa;
+      dbeta[n] = sb;
+    }
+  }
   /* dw_r[n][j] = sum over b and t of dy (.) v */
   if (w_r && dw_r)
     for (int n = 0; n < N; ++n)

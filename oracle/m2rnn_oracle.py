@@ -33,10 +33,10 @@ def _bind(path):
     lib = ctypes.CDLL(path)
     dp = ctypes.POINTER(ctypes.c_double)
     lib.m2rnn_oracle_fwd.restype = ctypes.c_int
-    lib.m2rnn_oracle_fwd.argtypes = [ctypes.c_int] * 6 + [dp] * 9
+    lib.m2rnn_oracle_fwd.argtypes = [ctypes.c_int] * 6 + [dp] * 11
     lib.m2rnn_oracle_bwd.restype = ctypes.c_int
     lib.m2rnn_oracle_bwd.argtypes = ([ctypes.c_int] * 6 + [dp] * 7 + [ctypes.c_double]
-                                     + [dp] * 9)
+                                     + [dp] * 13)
     lib.m2rnn_oracle_num_threads.restype = ctypes.c_int
     return lib
 
@@ -69,10 +69,11 @@ def _shapes(q, v):
     return B, T, N, Nqk, K, V
 
 
-def fwd(q, k, v, f, W, H0=None, w_r=None, _lib=None):
+def fwd(q, k, v, f, W, H0=None, w_r=None, gate=None, _lib=None):
     """y [B,T,N,V], HT [B,N,K,V] from q,k [B,T,Nqk,K], v [B,T,N,V], f [B,T,N],
     W [N,V,V], H0 [B,N,K,V] or None (zero state); w_r [N,V] or None adds the
-    residual w_r (.) v_t to y_t."""
+    residual w_r (.) v_t to y_t; gate = (alpha [N], beta [N]) makes f the input of
+    the forget-gate function psi instead of the gate value."""
     q = np.asarray(q)
     v = np.asarray(v)
     B, T, N, Nqk, K, V = _shapes(q, v)
@@ -83,21 +84,25 @@ def fwd(q, k, v, f, W, H0=None, w_r=None, _lib=None):
     Wa, Wp = _in(W, (N, V, V))
     Ha, Hp = _in(H0, (B, N, K, V))
     ra, rp = _in(w_r, (N, V))
+    aa, ap = _in(None if gate is None else gate[0], (N,))
+    ba, bp = _in(None if gate is None else gate[1], (N,))
     y = np.zeros((B, T, N, V))
     HT = np.zeros((B, N, K, V))
     dp = ctypes.POINTER(ctypes.c_double)
     rc = (_lib or _load()).m2rnn_oracle_fwd(
-        B, T, N, Nqk, K, V, qp, kp, vp, fp, Wp, Hp, rp,
+        B, T, N, Nqk, K, V, qp, kp, vp, fp, Wp, Hp, rp, ap, bp,
         y.ctypes.data_as(dp), HT.ctypes.data_as(dp))
     if rc != 0:
         raise RuntimeError("m2rnn_oracle_fwd failed with code %d" % rc)
     return y, HT
 
 
-def bwd(q, k, v, f, W, H0, dy, dHT=None, w_r=None, clip=0.0, _lib=None):
+def bwd(q, k, v, f, W, H0, dy, dHT=None, w_r=None, clip=0.0, gate=None, _lib=None):
     """Gradients (dq, dk, dv, df, dW, dH0) of  sum(y*dy) + sum(HT*dHT); with
     w_r [N,V] the residual is part of y and dw_r is appended to the result;
-    clip > 0 clamps the state gradient handed from each step to the one before."""
+    clip > 0 clamps the state gradient handed from each step to the one before;
+    gate = (alpha, beta): f is the gate function's input, df is the gradient with
+    respect to it, and (dalpha, dbeta) are appended to the result."""
     q = np.asarray(q)
     v = np.asarray(v)
     B, T, N, Nqk, K, V = _shapes(q, v)
@@ -111,6 +116,10 @@ def bwd(q, k, v, f, W, H0, dy, dHT=None, w_r=None, clip=0.0, _lib=None):
     dHa, dHp = _in(dHT, (B, N, K, V))
     ra, rp = _in(w_r, (N, V))
     dw_r = np.zeros((N, V))
+    aa, ap = _in(None if gate is None else gate[0], (N,))
+    ba, bp = _in(None if gate is None else gate[1], (N,))
+    dalpha = np.zeros(N)
+    dbeta = np.zeros(N)
     dq = np.zeros((B, T, Nqk, K))
     dk = np.zeros((B, T, Nqk, K))
     dv = np.zeros((B, T, N, V))
@@ -119,15 +128,18 @@ def bwd(q, k, v, f, W, H0, dy, dHT=None, w_r=None, clip=0.0, _lib=None):
     dH0 = np.zeros((B, N, K, V))
     dp = ctypes.POINTER(ctypes.c_double)
     rc = (_lib or _load()).m2rnn_oracle_bwd(
-        B, T, N, Nqk, K, V, qp, kp, vp, fp, Wp, Hp, rp, float(clip), dyp, dHp,
+        B, T, N, Nqk, K, V, qp, kp, vp, fp, Wp, Hp, rp, float(clip), ap, bp, dyp, dHp,
         dq.ctypes.data_as(dp), dk.ctypes.data_as(dp), dv.ctypes.data_as(dp),
         df.ctypes.data_as(dp), dW.ctypes.data_as(dp), dH0.ctypes.data_as(dp),
-        dw_r.ctypes.data_as(dp))
+        dw_r.ctypes.data_as(dp), dalpha.ctypes.data_as(dp), dbeta.ctypes.data_as(dp))
     if rc != 0:
         raise RuntimeError("m2rnn_oracle_bwd failed with code %d" % rc)
+    out = (dq, dk, dv, df, dW, dH0)
     if w_r is not None:
-        return dq, dk, dv, df, dW, dH0, dw_r
-    return dq, dk, dv, df, dW, dH0
+        out = out + (dw_r,)
+    if gate is not None:
+        out = out + (dalpha, dbeta)
+    return out
 
 
 def variant(path):

@@ -82,7 +82,8 @@ def torch_unrolled(c, need_grad=True, clip=0.0):
     the gradient that autograd sends along every recurrent edge (state handed from one
     step to the next, and H0 to the first step); the readout of a state is not on it."""
     import torch
-    names = ("q", "k", "v", "f", "W", "H0") + (("w_r",) if "w_r" in c else ())
+    names = (("q", "k", "v", "f", "W", "H0") + (("w_r",) if "w_r" in c else ())
+             + (("alpha", "beta") if "alpha" in c else ()))
     t = {n: (None if c[n] is None else
              torch.tensor(c[n], dtype=torch.float64, requires_grad=need_grad))
          for n in names}
@@ -106,7 +107,10 @@ def torch_unrolled(c, need_grad=True, clip=0.0):
             for s in range(T):
                 Hp = edge(H)
                 Z = torch.tanh(Hp @ t["W"][n] + torch.outer(t["k"][b, s, g], t["v"][b, s, n]))
-                H = t["f"][b, s, n] * Hp + (1 - t["f"][b, s, n]) * Z
+                fs = t["f"][b, s, n]
+                if "alpha" in t:  # the forget-gate function in its printed (power) form
+                    fs = (1 + torch.exp(fs + t["beta"][n])) ** (-t["alpha"][n])
+                H = fs * Hp + (1 - fs) * Z
                 yt = H.T @ t["q"][b, s, g]
                 if "w_r" in t:
                     yt = yt + t["w_r"][n] * t["v"][b, s, n]
@@ -192,6 +196,39 @@ def check_clipped_backward(fwd, bwd, tol=1e-11):
         _, _, g = torch_unrolled(c, clip=clip)
         for x, n in zip(got, ("q", "k", "v", "f", "W", "H0")):
             assert relerr(x, g[n]) < tol, n
+
+
+# --------------------------------------------------------------------------
+# The forget-gate function psi(x) = (1 + e^(x + beta))^(-alpha) in front of the scan.
+def check_gate_function(fwd, bwd, tol=1e-11):
+    for (B, N, T, K, V, Nqk) in [(2, 3, 4, 3, 4, None), (1, 4, 5, 4, 3, 2)]:
+        c = rand_case(500 + T, B, T, N, K, V, Nqk=Nqk)
+        rng = np.random.default_rng(7)
+        x = rng.standard_normal((B, T, N)) * 2.0
+        beta = rng.standard_normal(N)
+        alpha = rng.uniform(0.3, 2.5, N)
+        q, k, v, _, W, H0 = _args(c)
+        # the gate value in the printed power form, then the plain scan on it
+        f = (1.0 + np.exp(x + beta)) ** (-alpha)
+        y0, HT0 = fwd(q, k, v, f, W, H0)
+        y, HT = fwd(q, k, v, x, W, H0, gate=(alpha, beta))
+        assert relerr(y, y0) < 1e-13 and relerr(HT, HT0) < 1e-13
+        # alpha = 1 is a sigmoid of the reflected, shifted input
+        one = np.ones(N)
+        y1, _ = fwd(q, k, v, x, W, H0, gate=(one, beta))
+        y2, _ = fwd(q, k, v, 1.0 / (1.0 + np.exp(x + beta)), W, H0)
+        assert relerr(y1, y2) < 1e-13
+        # far out in both tails the gate is 0 or 1 and stays finite
+        yb, _ = fwd(q, k, v, np.where(x > 0, 800.0, -800.0), W, H0, gate=(alpha, beta))
+        yc, _ = fwd(q, k, v, np.where(x > 0, 0.0, 1.0), W, H0)
+        assert np.isfinite(yb).all() and relerr(yb, yc) < 1e-13
+        # gradients by reverse-mode autodiff through the power form
+        c2 = dict(c, f=x, alpha=alpha, beta=beta)
+        _, _, g = torch_unrolled(c2)
+        got = bwd(q, k, v, x, W, H0, c["dy"], c["dHT"], gate=(alpha, beta))
+        assert len(got) == 8
+        for xg, n in zip(got, ("q", "k", "v", "f", "W", "H0", "alpha", "beta")):
+            assert relerr(xg, g[n]) < tol, n
 
 
 # --------------------------------------------------------------------------
@@ -407,4 +444,5 @@ ALL_CHECKS = [
     check_gate_limits, check_segment_chaining, check_row_and_column_structure,
     check_state_bound, check_backward_linearity, check_empty_sequence,
     check_residual_T1_closed_form, check_residual_autograd, check_clipped_backward,
+    check_gate_function,
 ]

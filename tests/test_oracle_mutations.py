@@ -60,6 +60,15 @@ MUTATIONS = {
         ("G[i * V + j] = qt[i] * dyt[j] + C[i * V + j];",
          "{ G[i * V + j] = qt[i] * dyt[j] + C[i * V + j]; if (clip > 0.0) G[i * V + j] = "
          "G[i * V + j] > clip ? clip : (G[i * V + j] < -clip ? -clip : G[i * V + j]); }"),
+    "gate_exponent_sign":
+        ("return exp(-alpha[n] * softplus(x + beta[n]));", "return exp(alpha[n] * softplus(x + beta[n]));"),
+    "gate_beta_not_added":
+        ("return exp(-alpha[n] * softplus(x + beta[n]));", "return exp(-alpha[n] * softplus(x));"),
+    "gate_dx_misses_alpha":
+        ("const double dx = -g * alpha[n] * psi / (1.0 + exp(-u));",
+         "const double dx = -g * psi / (1.0 + exp(-u));"),
+    "gate_dalpha_uses_sigmoid":
+        ("sa += -g * psi * sp;", "sa += -g * psi / (1.0 + exp(-u));"),
     "readout_before_update":
         ("acc += H[i * V + j] * qt[i];", "acc += S[i * V + j] * qt[i];"),
 }
