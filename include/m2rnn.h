@@ -151,11 +151,25 @@ m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k,
  *              (f_t G_t + dS_t W^T) is clamped to [-grad_clip, grad_clip] as soon as it
  *              is formed, before q dy^T of step t-1 is added; dH0 is the clamped value,
  *              dHT is used as given.  <= 0: off, gradients are exact.  Forward ignores it.
+ *   gate_alpha, gate_beta   [N] fp32 each, device: parameters of the forget-gate function of
+ *              the "Forget Gate" section, psi(x) = (1 + e^(x + beta_n))^(-alpha_n).  When
+ *              gate_alpha is given (gate_beta is then required), the argument `f` of both
+ *              calls holds the gate's INPUT x [B,T,N] fp32 and the kernels apply psi where
+ *              they stage f; in the backward `df` then receives the gradient with respect
+ *              to x, and dgate_alpha / dgate_beta the gradients of the parameters summed
+ *              over b and t.  NULL: `f` is the gate value (the plain calls).
+ *   dgate_alpha, dgate_beta [N] fp32 each, device, out; read by m2rnn_bwd_opt only,
+ *              required there when gate_alpha is given.
+ * Zero-initialise the struct, then fill what is used.
  */
 typedef struct {
   const void *w_r;
   float *dw_r;
   float grad_clip;
+  const float *gate_alpha;
+  const float *gate_beta;
+  float *dgate_alpha;
+  float *dgate_beta;
 } m2rnn_opts;
 
 /* m2rnn_fwd / m2rnn_bwd with options; opts == NULL behaves exactly like the plain calls.

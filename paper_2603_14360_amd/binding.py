@@ -26,7 +26,9 @@ class m2rnn_desc(ctypes.Structure):
 
 
 class m2rnn_opts(ctypes.Structure):
-    _fields_ = [("w_r", ctypes.c_void_p), ("dw_r", ctypes.c_void_p), ("grad_clip", ctypes.c_float)]
+    _fields_ = [("w_r", ctypes.c_void_p), ("dw_r", ctypes.c_void_p), ("grad_clip", ctypes.c_float),
+                ("gate_alpha", ctypes.c_void_p), ("gate_beta", ctypes.c_void_p),
+                ("dgate_alpha", ctypes.c_void_p), ("dgate_beta", ctypes.c_void_p)]
 
 
 class M2RNNError(RuntimeError):
@@ -133,10 +135,12 @@ def m2rnn_bwd(desc, q, k, v, f, W, H0, ckpt, dy, dHT, dq, dk, dv, df, dW, dH0, w
     return rc
 
 
-def make_opts(w_r=None, dw_r=None, grad_clip=0.0):
-    """m2rnn_opts from torch tensors (or None)."""
-    return m2rnn_opts(None if w_r is None else w_r.data_ptr(),
-                      None if dw_r is None else dw_r.data_ptr(), float(grad_clip))
+def make_opts(w_r=None, dw_r=None, grad_clip=0.0, gate=None, dgate=None):
+    """m2rnn_opts from torch tensors (or None); gate = (alpha, beta), dgate = (dalpha, dbeta)."""
+    p = lambda x: None if x is None else x.data_ptr()
+    ga, gb = gate if gate is not None else (None, None)
+    da, db = dgate if dgate is not None else (None, None)
+    return m2rnn_opts(p(w_r), p(dw_r), float(grad_clip), p(ga), p(gb), p(da), p(db))
 
 
 def m2rnn_fwd_opt(desc, opts, q, k, v, f, W, H0, y, HT, ckpt, workspace, stream=None, check=True):
@@ -197,20 +201,23 @@ class Scan:
     def _stream(self):
         return self.torch.cuda.current_stream().cuda_stream
 
-    def fwd(self, q, k, v, f, W, H0=None, w_r=None):
-        """w_r [N,V] (io dtype): adds the residual w_r (.) v_t to y_t."""
-        if w_r is None:
+    def fwd(self, q, k, v, f, W, H0=None, w_r=None, gate=None):
+        """w_r [N,V] (io dtype): adds the residual w_r (.) v_t to y_t.  gate = (alpha, beta)
+        [N] fp32 each: f is the input of the forget-gate function."""
+        if w_r is None and gate is None:
             m2rnn_fwd(self.desc, q, k, v, f, W, H0, self.y, self.HT, self.ckpt, self.workspace,
                       stream=self._stream())
         else:
-            m2rnn_fwd_opt(self.desc, make_opts(w_r=w_r), q, k, v, f, W, H0, self.y, self.HT,
-                          self.ckpt, self.workspace, stream=self._stream())
+            m2rnn_fwd_opt(self.desc, make_opts(w_r=w_r, gate=gate), q, k, v, f, W, H0, self.y,
+                          self.HT, self.ckpt, self.workspace, stream=self._stream())
         return self.y, self.HT
 
-    def bwd(self, q, k, v, f, W, H0, dy, dHT=None, use_ckpt=True, w_r=None, grad_clip=0.0):
-        """With w_r the result has a seventh entry, dw_r [N,V] fp32."""
+    def bwd(self, q, k, v, f, W, H0, dy, dHT=None, use_ckpt=True, w_r=None, grad_clip=0.0,
+            gate=None):
+        """With w_r the result has a further entry, dw_r [N,V] fp32; with gate two more,
+        dalpha and dbeta [N] fp32 (and df is the gradient of the gate's input)."""
         ck = self.ckpt if use_ckpt else None
-        if w_r is None and not grad_clip > 0:
+        if w_r is None and gate is None and not grad_clip > 0:
             m2rnn_bwd(self.desc, q, k, v, f, W, H0, ck, dy, dHT, self.dq, self.dk, self.dv,
                       self.df, self.dW, self.dH0, self.workspace, stream=self._stream())
             return self.dq, self.dk, self.dv, self.df, self.dW, self.dH0
@@ -218,8 +225,16 @@ class Scan:
         if w_r is not None:
             dw_r = self.torch.empty((self.desc.N, self.desc.V), dtype=self.torch.float32,
                                     device=self.dW.device)
-        m2rnn_bwd_opt(self.desc, make_opts(w_r, dw_r, grad_clip), q, k, v, f, W, H0, ck, dy, dHT,
-                      self.dq, self.dk, self.dv, self.df, self.dW, self.dH0, self.workspace,
-                      stream=self._stream())
+        dgate = None
+        if gate is not None:
+            dgate = tuple(self.torch.empty((self.desc.N,), dtype=self.torch.float32,
+                                           device=self.dW.device) for _ in range(2))
+        m2rnn_bwd_opt(self.desc, make_opts(w_r, dw_r, grad_clip, gate, dgate), q, k, v, f, W, H0,
+                      ck, dy, dHT, self.dq, self.dk, self.dv, self.df, self.dW, self.dH0,
+                      self.workspace, stream=self._stream())
         out = (self.dq, self.dk, self.dv, self.df, self.dW, self.dH0)
-        return out if dw_r is None else out + (dw_r,)
+        if dw_r is not None:
+            out = out + (dw_r,)
+        if dgate is not None:
+            out = out + dgate
+        return out

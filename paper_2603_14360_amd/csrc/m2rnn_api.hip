@@ -124,7 +124,7 @@ size_t m2rnn_workspace_bytes(const m2rnn_desc *desc, int bwd) {
     // room for the backward's own checkpoint pass (used when ckpt == NULL)
     const size_t fwd_need = family_ws(desc, C, 0);
     need = align256(need > fwd_need ? need : fwd_need) + align256(ckpt_bytes(desc, C)) +
-           residual_dw_r_scratch_bytes(desc->N, desc->V);
+           residual_dw_r_scratch_bytes(desc->N, desc->V) + gate_scratch_bytes(desc->N);
   }
   return need;
 }
@@ -149,7 +149,9 @@ m2rnn_status m2rnn_fwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
   if (!W) return M2RNN_ERR_NULL;
   if (steps && (!q || !k || !v || !f || !y)) return M2RNN_ERR_NULL;
   const void *w_r = opts ? opts->w_r : nullptr;
-  const void *ptrs[] = {q, k, v, f, W, H0, y, HT, ckpt, workspace, w_r};
+  const float *ga = opts ? opts->gate_alpha : nullptr, *gb = ga ? opts->gate_beta : nullptr;
+  if (ga && !gb) return M2RNN_ERR_NULL;
+  const void *ptrs[] = {q, k, v, f, W, H0, y, HT, ckpt, workspace, w_r, ga, gb};
   for (const void *p : ptrs)
     if (misaligned(p)) return M2RNN_ERR_ALIGN;
   const size_t need = family_ws(desc, C, 0);
@@ -161,7 +163,7 @@ m2rnn_status m2rnn_fwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
   a.C = C; a.io = desc->io;
   a.q = q; a.k = k; a.v = v; a.W = W; a.f = f; a.H0 = H0;
   a.y = y; a.HT = HT; a.ckpt = ckpt; a.write_y = 1; a.ws = (char *)workspace;
-  a.w_r = w_r;
+  a.w_r = w_r; a.gate_alpha = ga; a.gate_beta = gb;
   hipStream_t s = (hipStream_t)hip_stream;
   const hipError_t e = run_fwd(desc, a, s);
   return e == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
@@ -191,8 +193,11 @@ m2rnn_status m2rnn_bwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
   const void *w_r = opts ? opts->w_r : nullptr;
   float *dw_r = w_r ? opts->dw_r : nullptr;
   if (w_r && !dw_r) return M2RNN_ERR_NULL;
-  const void *ptrs[] = {q,  k,  v,  f,  W,   H0,        ckpt, dy,  dHT,
-                        dq, dk, dv, df, dW, dH0, workspace, w_r,  dw_r};
+  const float *ga = opts ? opts->gate_alpha : nullptr, *gb = ga ? opts->gate_beta : nullptr;
+  float *dga = ga ? opts->dgate_alpha : nullptr, *dgb = ga ? opts->dgate_beta : nullptr;
+  if (ga && (!gb || !dga || !dgb)) return M2RNN_ERR_NULL;
+  const void *ptrs[] = {q,  k,  v,  f,   W,   H0,        ckpt, dy,   dHT, dq, dk,
+                        dv, df, dW, dH0, workspace, w_r, dw_r, ga,  gb,  dga, dgb};
   for (const void *p : ptrs)
     if (misaligned(p)) return M2RNN_ERR_ALIGN;
   const size_t need = m2rnn_workspace_bytes(desc, 1);
@@ -203,7 +208,8 @@ m2rnn_status m2rnn_bwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
   const Family fam = family_of(desc);
   char *ws = (char *)workspace;
   const size_t dwr_bytes = residual_dw_r_scratch_bytes(desc->N, desc->V);
-  const size_t main_bytes = need - align256(ckpt_bytes(desc, C)) - dwr_bytes;
+  const size_t gate_bytes = gate_scratch_bytes(desc->N);
+  const size_t main_bytes = need - align256(ckpt_bytes(desc, C)) - dwr_bytes - gate_bytes;
   if (!ckpt && steps) {
     // The paper's pass 1, keeping one state per chunk: rerun the recurrence
     // from H0 without the readout, into the tail of the workspace.
@@ -213,7 +219,7 @@ m2rnn_status m2rnn_bwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
     fa.V = desc->V; fa.C = C; fa.io = desc->io;
     fa.q = q; fa.k = k; fa.v = v; fa.W = W; fa.f = f; fa.H0 = H0;
     fa.y = nullptr; fa.HT = nullptr; fa.ckpt = own; fa.write_y = 0; fa.ws = ws;
-    fa.w_r = nullptr;
+    fa.w_r = nullptr; fa.gate_alpha = ga; fa.gate_beta = gb;
     const hipError_t e = run_fwd(desc, fa, s);
     if (e != hipSuccess) return M2RNN_ERR_HIP;
     ckpt = own;
@@ -223,10 +229,13 @@ m2rnn_status m2rnn_bwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
   a.C = C; a.io = desc->io;
   a.q = q; a.k = k; a.v = v; a.W = W; a.dy = dy; a.f = f; a.H0 = H0; a.ckpt = ckpt; a.dHT = dHT;
   a.dq = dq; a.dk = dk; a.dv = dv; a.df = df; a.dW = dW; a.dH0 = dH0; a.ws = ws;
-  a.w_r = w_r; a.dw_r = dw_r; a.dwr_ws = (float *)(ws + need - dwr_bytes);
+  a.w_r = w_r; a.dw_r = dw_r; a.dwr_ws = (float *)(ws + need - gate_bytes - dwr_bytes);
   a.clip = opts ? opts->grad_clip : 0.f;
+  a.gate_alpha = ga; a.gate_beta = gb; a.dgate_alpha = dga; a.dgate_beta = dgb;
+  a.gate_ws = (float *)(ws + need - gate_bytes);
   hipError_t e = fam == kMfma ? mfma_bwd(a, s) : generic_bwd(a, s);
   if (e == hipSuccess && w_r) e = residual_dw_r(a, s);
+  if (e == hipSuccess && ga) e = gate_backward(a, s);
   return e == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
 }
 

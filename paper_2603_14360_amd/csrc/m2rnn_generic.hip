@@ -121,7 +121,8 @@ __global__ void __launch_bounds__(kMaxThreads) gen_fwd_kernel(FwdArgs a, const f
       qs[e] = to_f32<IO>(q[qk_off + e]);
     }
     for (int e = tid; e < V; e += nt) vs[e] = to_f32<IO>(v[v_off + e]);
-    const float f = a.f[((size_t)b * T + t) * N + n];
+    float f = a.f[((size_t)b * T + t) * N + n];
+    if (a.gate_alpha) f = gate_psi(f, a.gate_alpha[n], a.gate_beta[n]);
     __syncthreads();
     step_elements<false>(Hs, Wf, ks, vs, f, K, V, KV, hn, nullptr);
     __syncthreads();
@@ -206,7 +207,8 @@ __global__ void __launch_bounds__(kMaxThreads)
       const size_t v_off = (((size_t)b * T + t) * N + n) * V;
       for (int e = tid; e < K; e += nt) ks[e] = to_f32<IO>(k[qk_off + e]);
       for (int e = tid; e < V; e += nt) vs[e] = to_f32<IO>(v[v_off + e]);
-      const float f = a.f[((size_t)b * T + t) * N + n];
+      float f = a.f[((size_t)b * T + t) * N + n];
+    if (a.gate_alpha) f = gate_psi(f, a.gate_alpha[n], a.gate_beta[n]);
       __syncthreads();
       step_elements<false>(Hs, Wf, ks, vs, f, K, V, KV, hn, nullptr);
       __syncthreads();
@@ -231,7 +233,8 @@ __global__ void __launch_bounds__(kMaxThreads)
         vs[e] = to_f32<IO>(v[v_off + e]);
         dys[e] = to_f32<IO>(dy[v_off + e]);
       }
-      const float f = a.f[((size_t)b * T + t) * N + n];
+      float f = a.f[((size_t)b * T + t) * N + n];
+    if (a.gate_alpha) f = gate_psi(f, a.gate_alpha[n], a.gate_beta[n]);
       __syncthreads();
       // recompute Z_t and H_t exactly as the forward did
       step_elements<true>(Hs, Wf, ks, vs, f, K, V, KV, hn, z);
@@ -489,6 +492,58 @@ hipError_t generic_fwd(const FwdArgs &a, hipStream_t s) {
 
 hipError_t generic_bwd(const BwdArgs &a, hipStream_t s) {
   return a.io == 0 ? run_bwd<float>(a, s) : run_bwd<__hip_bfloat16>(a, s);
+}
+
+// Chain rule through the gate function.  df holds dL/d(gate value) g; with u = x + beta,
+// psi = exp(-alpha softplus(u)):  dL/dx = dL/dbeta-term = -g alpha psi sigmoid(u),
+// dL/dalpha-term = -g psi softplus(u).  Stage 1: block s handles the (b, t) rows s, s + S, ...
+// in increasing order, thread n one head; stage 2 adds the S partial rows in increasing s.
+constexpr int kGateStages = 256;
+__global__ void gate_bwd_stage1_kernel(float *__restrict__ df, const float *__restrict__ x,
+                                       const float *__restrict__ alpha,
+                                       const float *__restrict__ beta, float *__restrict__ part,
+                                       size_t BT, int N) {
+  for (int n = threadIdx.x; n < N; n += blockDim.x) {
+    const float al = alpha[n], be = beta[n];
+    float sa = 0.f, sb = 0.f;
+    for (size_t r = blockIdx.x; r < BT; r += gridDim.x) {
+      const float u = x[r * N + n] + be;
+      const float sp = fmaxf(u, 0.f) + log1pf(expf(-fabsf(u)));
+      const float psi = expf(-al * sp);
+      const float g = df[r * N + n];
+      const float dx = -g * al * psi / (1.f + expf(-u));
+      sa = fmaf(-g * psi, sp, sa);
+      sb += dx;
+      df[r * N + n] = dx;
+    }
+    part[((size_t)blockIdx.x * 2 + 0) * N + n] = sa;
+    part[((size_t)blockIdx.x * 2 + 1) * N + n] = sb;
+  }
+}
+__global__ void gate_bwd_stage2_kernel(const float *__restrict__ part, float *__restrict__ dalpha,
+                                       float *__restrict__ dbeta, int S, int N) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  float sa = 0.f, sb = 0.f;
+  for (int p = 0; p < S; ++p) {
+    sa += part[((size_t)p * 2 + 0) * N + n];
+    sb += part[((size_t)p * 2 + 1) * N + n];
+  }
+  dalpha[n] = sa;
+  dbeta[n] = sb;
+}
+
+size_t gate_scratch_bytes(int N) { return align256((size_t)kGateStages * 2 * N * sizeof(float)); }
+
+hipError_t gate_backward(const BwdArgs &a, hipStream_t s) {
+  const size_t BT = (size_t)a.B * a.T;
+  const int S = BT < (size_t)kGateStages ? (int)BT : kGateStages;
+  if (S > 0)
+    hipLaunchKernelGGL(gate_bwd_stage1_kernel, dim3(S), dim3(a.N < 64 ? 64 : 128), 0, s, a.df,
+                       a.f, a.gate_alpha, a.gate_beta, a.gate_ws, BT, a.N);
+  hipLaunchKernelGGL(gate_bwd_stage2_kernel, dim3((a.N + 63) / 64), dim3(64), 0, s,
+                     (const float *)a.gate_ws, a.dgate_alpha, a.dgate_beta, S, a.N);
+  return hipGetLastError();
 }
 
 size_t residual_dw_r_scratch_bytes(int N, int V) {

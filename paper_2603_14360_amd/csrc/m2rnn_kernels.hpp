@@ -18,6 +18,7 @@ struct FwdArgs {
   int write_y;       // 0: checkpoint-only pass (the backward's pass 1)
   char *ws;          // workspace base (may be null when nothing is needed)
   const void *w_r;   // [N,V] io dtype: y_t += w_r (.) v_t; null = no residual
+  const float *gate_alpha, *gate_beta;  // [N] each: f holds the input of the gate function; null = f is the gate value
 };
 
 struct BwdArgs {
@@ -31,6 +32,9 @@ struct BwdArgs {
   float *dw_r;       // [N,V] fp32 out, with w_r
   float *dwr_ws;     // scratch of residual_dw_r_scratch_bytes() for dw_r
   float clip;        // > 0: clamp of the carried state gradient; <= 0: off
+  const float *gate_alpha, *gate_beta;  // as in FwdArgs; then df is finished by gate_backward()
+  float *dgate_alpha, *dgate_beta;      // [N] fp32 out
+  float *gate_ws;                       // scratch of gate_scratch_bytes()
 };
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -46,6 +50,18 @@ hipError_t generic_bwd(const BwdArgs &a, hipStream_t s);
 // dw_r[n][j] = sum over b, t of dy (.) v in a fixed order (two stages through `scratch`)
 size_t residual_dw_r_scratch_bytes(int N, int V);
 hipError_t residual_dw_r(const BwdArgs &a, hipStream_t s);
+
+// Forget-gate function of the paper's "Forget Gate" section, psi(x) = (1 + e^(x + beta))^(-alpha),
+// evaluated where a kernel stages f (one lane per step): exp(-alpha softplus(x + beta)).
+__device__ __forceinline__ float gate_psi(float x, float alpha, float beta) {
+  const float u = x + beta;
+  const float sp = fmaxf(u, 0.f) + log1pf(expf(-fabsf(u)));
+  return expf(-alpha * sp);
+}
+// Chain rule through psi after a backward scan: df (in: dL/d gate value) -> dL/dx in place,
+// dalpha, dbeta summed over b, t in a fixed order (two stages through `gate_ws`).
+size_t gate_scratch_bytes(int N);
+hipError_t gate_backward(const BwdArgs &a, hipStream_t s);
 
 // ---- matrix-core path (bf16 io, fp16 MFMA operands, fp32 state) ----
 bool mfma_supported(int K, int V);

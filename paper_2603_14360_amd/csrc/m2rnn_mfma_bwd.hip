@@ -268,6 +268,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         }
       }
       if (ef < CMAX) {
+        if (a.gate_alpha) rf = gate_psi(rf, a.gate_alpha[n], a.gate_beta[n]);
         fA[ef * 4 + 0] = rf;
         fA[ef * 4 + 1] = kC * (1.f - rf);
       }
@@ -514,6 +515,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       if (lane == 0) atomicMax(&scl[4 * set_now + 2], __builtin_bit_cast(int, md));
     }
     if (ef < CMAX) {
+      if (a.gate_alpha) rf = gate_psi(rf, a.gate_alpha[n], a.gate_beta[n]);
       const float gm = 1.f - rf;
       const h2_t m2 = {(_Float16)(gm * (-kInvC * kInvC)), (_Float16)(gm * (-kInvC * kInvC))};
       const h2_t g2 = {(_Float16)gm, (_Float16)gm};

@@ -181,6 +181,7 @@ __global__ void __launch_bounds__(TL::THREADS)
       }
     }
     if (tid < TB) {
+      if (a.gate_alpha) rf = gate_psi(rf, a.gate_alpha[n], a.gate_beta[n]);
       const float gp = kC * (1.f - rf);
       sm.fS[buf][tid][0] = rf;
       sm.fS[buf][tid][1] = gp;

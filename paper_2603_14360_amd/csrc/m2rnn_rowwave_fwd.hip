@@ -160,6 +160,7 @@ __global__ void __launch_bounds__(RW::THREADS) rowwave_fwd_kernel(FwdArgs a) {
       if (idx < TB * V) vH(buf)[idx] = (_Float16)bf16_to_f32(rv[m]);
     }
     if (tid < TB) {
+      if (a.gate_alpha) rf = gate_psi(rf, a.gate_alpha[n], a.gate_beta[n]);
       const float gp = kC * (1.f - rf);
       fS(buf)[tid * 4 + 0] = rf;
       fS(buf)[tid * 4 + 1] = gp;

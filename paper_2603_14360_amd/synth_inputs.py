@@ -128,6 +128,20 @@ def make_residual_weight(wl, N=None):
     return _store(rng.standard_normal((N, wl.V)), wl.io)
 
 
+def make_gate_inputs(wl, B=None, T=None, N=None):
+    """Inputs of the forget-gate function: x [B,T,N] ~ N(0, 2^2) (float32) in place of the gate
+    value, alpha ~ Uniform(0.3, 2.5) and beta ~ N(0, 1) per head, from a generator stream of
+    their own.  Returns (x, (alpha, beta))."""
+    B = wl.B if B is None else B
+    T = wl.T if T is None else T
+    N = wl.N if N is None else N
+    rng = np.random.default_rng([wl.seed, 104729])
+    x = (2.0 * rng.standard_normal((B, T, N))).astype(np.float32)
+    alpha = rng.uniform(0.3, 2.5, N).astype(np.float32)
+    beta = rng.standard_normal(N).astype(np.float32)
+    return x, (alpha, beta)
+
+
 def select_heads(inp, heads):
     """Restrict workload tensors to a list of heads; the recurrences of
     different heads are independent, so the oracle can be run on the selection

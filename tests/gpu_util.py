@@ -40,12 +40,17 @@ def run_gpu(inp, io, chunk=0, backward=True, use_ckpt=True, grad_clip=0.0):
     if inp.get("w_r") is not None:
         w_r = torch.from_numpy(np.ascontiguousarray(inp["w_r"], dtype=np.float32)).to("cuda").to(
             torch.bfloat16 if io == "bf16" else torch.float32)
-    y, HT = scan.fwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"], w_r=w_r)
+    gate = None
+    if inp.get("gate") is not None:
+        gate = tuple(torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)).to("cuda")
+                     for g in inp["gate"])
+    y, HT = scan.fwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"], w_r=w_r, gate=gate)
     out = {"y": to_np(y), "HT": to_np(HT)}
     if backward:
         g = scan.bwd(dev["q"], dev["k"], dev["v"], dev["f"], dev["W"], dev["H0"], dev["dy"],
-                     dev["dHT"], use_ckpt=use_ckpt, w_r=w_r, grad_clip=grad_clip)
-        for name, x in zip(GRAD_NAMES + ("dw_r",), g):
+                     dev["dHT"], use_ckpt=use_ckpt, w_r=w_r, grad_clip=grad_clip, gate=gate)
+        extra = (("dw_r",) if w_r is not None else ()) + (("dalpha", "dbeta") if gate else ())
+        for name, x in zip(GRAD_NAMES + extra, g):
             out[name] = to_np(x)
     torch.cuda.synchronize()
     return out
@@ -53,12 +58,14 @@ def run_gpu(inp, io, chunk=0, backward=True, use_ckpt=True, grad_clip=0.0):
 
 def run_oracle(inp, backward=True, grad_clip=0.0):
     args = [inp[n] for n in ("q", "k", "v", "f", "W")]
-    y, HT = oracle.fwd(*args, inp.get("H0"), w_r=inp.get("w_r"))
+    y, HT = oracle.fwd(*args, inp.get("H0"), w_r=inp.get("w_r"), gate=inp.get("gate"))
     out = {"y": y, "HT": HT}
     if backward:
         g = oracle.bwd(*args, inp.get("H0"), inp["dy"], inp.get("dHT"), w_r=inp.get("w_r"),
-                       clip=grad_clip)
-        out.update(dict(zip(GRAD_NAMES + ("dw_r",), g)))
+                       clip=grad_clip, gate=inp.get("gate"))
+        extra = ((("dw_r",) if inp.get("w_r") is not None else ())
+                 + (("dalpha", "dbeta") if inp.get("gate") is not None else ()))
+        out.update(dict(zip(GRAD_NAMES + extra, g)))
     return out
 
 

@@ -7,7 +7,8 @@ not, the register-resident forward, and the fp32 kernels."""
 import numpy as np
 import pytest
 
-from paper_2603_14360_amd.synth_inputs import WORKLOADS, Workload, make_inputs, make_residual_weight
+from paper_2603_14360_amd.synth_inputs import (WORKLOADS, Workload, make_gate_inputs, make_inputs,
+                                                make_residual_weight)
 import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
@@ -64,8 +65,33 @@ def test_clipped_backward(io, B, T, N, K, V, Nqk):
     _report(label, gu.compare(got, ref, gu.TOL[io], label=label))
 
 
+@pytest.mark.parametrize("io,B,T,N,K,V,Nqk", CASES)
+def test_gate_function(io, B, T, N, K, V, Nqk):
+    """f holds the input of psi(x) = (1 + e^(x + beta))^(-alpha); df is the gradient of x."""
+    label = "gate %s B%d T%d N%d K%d V%d Nqk%d" % (io, B, T, N, K, V, Nqk)
+    print("case", label, flush=True)
+    wl = _wl(io, B, T, N, K, V, Nqk, seed=B + T + K + V + 2)
+    inp = make_inputs(wl)
+    inp["f"], inp["gate"] = make_gate_inputs(wl)
+    got = gu.run_gpu(inp, io)
+    ref = gu.run_oracle(inp)
+    assert "dalpha" in got and "dbeta" in ref
+    _report(label, gu.compare(got, ref, gu.TOL[io], label=label))
+
+
+def test_gate_function_without_checkpoints_bf16():
+    """The backward's own checkpoint pass applies the gate function as well."""
+    wl = _wl("bf16", 2, 50, 3, 64, 64, 0, seed=91)
+    inp = make_inputs(wl)
+    inp["f"], inp["gate"] = make_gate_inputs(wl)
+    print("case gate, ckpt = NULL", flush=True)
+    got = gu.run_gpu(inp, "bf16", use_ckpt=False)
+    ref = gu.run_oracle(inp)
+    _report("gate no ckpt", gu.compare(got, ref, gu.TOL["bf16"], label="gate no ckpt"))
+
+
 def test_options_together_and_null_opts_bf16():
-    """Residual and clipping in one call; a NULL options pointer and an all-zero options
+    """Residual, gate function and clipping in one call; a NULL options pointer and an all-zero options
     struct give exactly the plain entry points' results."""
     import torch
     from paper_2603_14360_amd import binding as mb
@@ -73,6 +99,7 @@ def test_options_together_and_null_opts_bf16():
     inp = make_inputs(wl)
     print("case options together", flush=True)
     both = dict(inp, w_r=make_residual_weight(wl))
+    both["f"], both["gate"] = make_gate_inputs(wl)
     free = gu.run_oracle(both)
     clip = 0.3 * float(np.abs(free["dH0"]).max())
     got = gu.run_gpu(both, "bf16", grad_clip=clip)
