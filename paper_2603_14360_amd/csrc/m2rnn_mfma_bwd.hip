@@ -402,6 +402,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
 
   // =======================================================================
   // team B: sweep chunk nck-it out of stash[(it-1) & 1], it = 1 .. nck
+  // This team's step is the longer one (the recompute team waits for it at every barrier),
+  // so its waves get the higher issue priority on the SIMDs they share with that team.
+  __builtin_amdgcn_s_setprio(3);
   FragT wtf[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks)
