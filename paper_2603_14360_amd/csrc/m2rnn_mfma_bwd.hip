@@ -182,8 +182,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     float rf = 1.f;
     float hck[4];
     // Global addresses of the staged vectors: a wave-uniform 64-bit base per tensor (batch
-    // element, head) plus a 32-bit element offset = per-thread constant + chunk start * row
-    // stride.  (One batch element of a tensor stays far below 2^32 elements.)
+    // element, head, chunk start) plus a 32-bit byte offset inside the chunk.
     const bf16_raw *const kbase = kg + ((size_t)b * T * a.Nqk + g) * K + row_base;
     const bf16_raw *const vbase = vg + ((size_t)b * T * N + n) * V;
     const bf16_raw *const dybase = dyg + ((size_t)b * T * N + n) * V;
@@ -204,22 +203,22 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       asm volatile("" : "+v"(tl));
       {
         const int e = (tl - SH_K) & (THREADS - 1), s = e / RL, p = e - s * RL;
-        const uint32_t off = 2u * ((uint32_t)(t0 + s) * kstride + 8u * p);
-        rk = (e < QI && s < len) ? *(const u4_t *)((const char *)kbase + off) : zero_u4;
+        const uint32_t off = 2u * ((uint32_t)s * kstride + 8u * p);
+        rk = (e < QI && s < len) ? *(const u4_t *)((const char *)(kbase + (size_t)t0 * kstride) + off) : zero_u4;
       }
       {
         const int e = (tl - SH_V) & (THREADS - 1), s = e / VL, p = e - s * VL;
-        const uint32_t off = 2u * ((uint32_t)(t0 + s) * vstride + 8u * p);
-        rv = (e < VI && s < len) ? *(const u4_t *)((const char *)vbase + off) : zero_u4;
+        const uint32_t off = 2u * ((uint32_t)s * vstride + 8u * p);
+        rv = (e < VI && s < len) ? *(const u4_t *)((const char *)(vbase + (size_t)t0 * vstride) + off) : zero_u4;
       }
       {
         const int e = (tl - SH_DY) & (THREADS - 1), s = e / VL, p = e - s * VL;
-        const uint32_t off = 2u * ((uint32_t)(t0 + s) * vstride + 8u * p);
-        rdy = (e < VI && s < len) ? *(const u4_t *)((const char *)dybase + off) : zero_u4;
+        const uint32_t off = 2u * ((uint32_t)s * vstride + 8u * p);
+        rdy = (e < VI && s < len) ? *(const u4_t *)((const char *)(dybase + (size_t)t0 * vstride) + off) : zero_u4;
       }
       {
         const int e = (tl - SH_F) & (THREADS - 1);
-        rf = (e < len) ? *(const float *)((const char *)fbase + 4u * ((uint32_t)(t0 + e) * (uint32_t)N))
+        rf = (e < len) ? *(const float *)((const char *)(fbase + (size_t)t0 * N) + 4u * ((uint32_t)e * (uint32_t)N))
                        : 1.f;
       }
       {
@@ -452,27 +451,27 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     asm volatile("" : "+v"(tl));
     {
       const int e = (tl - SH_Q) & (THREADS - 1), s = e / RL, p = e - s * RL;
-      const uint32_t off = 2u * ((uint32_t)(t0 + s) * kstride + 8u * p);
-      rq = (e < QI && s < len) ? *(const u4_t *)((const char *)qbase + off) : zero_u4;
+      const uint32_t off = 2u * ((uint32_t)s * kstride + 8u * p);
+      rq = (e < QI && s < len) ? *(const u4_t *)((const char *)(qbase + (size_t)t0 * kstride) + off) : zero_u4;
     }
     {
       const int e = (tl - SH_K) & (THREADS - 1), s = e / RL, p = e - s * RL;
-      const uint32_t off = 2u * ((uint32_t)(t0 + s) * kstride + 8u * p);
-      rk = (e < QI && s < len) ? *(const u4_t *)((const char *)kbase + off) : zero_u4;
+      const uint32_t off = 2u * ((uint32_t)s * kstride + 8u * p);
+      rk = (e < QI && s < len) ? *(const u4_t *)((const char *)(kbase + (size_t)t0 * kstride) + off) : zero_u4;
     }
     {
       const int e = (tl - SH_V) & (THREADS - 1), s = e / VL, p = e - s * VL;
-      const uint32_t off = 2u * ((uint32_t)(t0 + s) * vstride + 8u * p);
-      rv = (e < VI && s < len) ? *(const u4_t *)((const char *)vbase + off) : zero_u4;
+      const uint32_t off = 2u * ((uint32_t)s * vstride + 8u * p);
+      rv = (e < VI && s < len) ? *(const u4_t *)((const char *)(vbase + (size_t)t0 * vstride) + off) : zero_u4;
     }
     {
       const int e = (tl - SH_DY) & (THREADS - 1), s = e / VL, p = e - s * VL;
-      const uint32_t off = 2u * ((uint32_t)(t0 + s) * vstride + 8u * p);
-      rdy = (e < VI && s < len) ? *(const u4_t *)((const char *)dybase + off) : zero_u4;
+      const uint32_t off = 2u * ((uint32_t)s * vstride + 8u * p);
+      rdy = (e < VI && s < len) ? *(const u4_t *)((const char *)(dybase + (size_t)t0 * vstride) + off) : zero_u4;
     }
     {
       const int e = (tl - SH_F) & (THREADS - 1);
-      rf = (e < len) ? *(const float *)((const char *)fbase + 4u * ((uint32_t)(t0 + e) * (uint32_t)N))
+      rf = (e < len) ? *(const float *)((const char *)(fbase + (size_t)t0 * N) + 4u * ((uint32_t)e * (uint32_t)N))
                      : 1.f;
     }
   };
