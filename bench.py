@@ -23,8 +23,10 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# Algorithmic vector-ALU work per state element per time step:
-# (plain fp32 ops, transcendental ops)
+# Algorithmic vector-ALU work per state element per time step, (plain fp32 ops, transcendental
+# ops).  Forward: k.v FMA, 1 + e, gate FMAs, readout, convert = 7, plus exp2 and rcp of the
+# tanh.  Backward given H_{t-1}: recompute 3, dq 1, G 1, df 2, dS 3, carry 1, dk + dv 2,
+# converts 1 = 14, plus exp2 and rcp.  The chunk recompute of the backward is not counted.
 ALU_OPS = {"fwd": (7, 2), "bwd": (14, 2)}
 TRANS_SLOTS = 2                       # issue slots of v_exp_f32 / v_rcp_f32 relative to v_fma_f32
 PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9  # lane-ops per second, packed fp32 not used
