@@ -537,7 +537,6 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     set_now = it & 1;  // maxima that decide this chunk's scale
     if (active) {
       stage_store();
-      stage_load(ck > 0 ? ck - 1 : 0);  // (unconditional: see team A)
     }
     lds_barrier();  // P: this chunk's stash entries were completed by team A in the previous iteration
     // the other set was read one iteration ago and is filled again from the end of this one
@@ -574,6 +573,11 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
                    // step instead of being kept in registers for every s of an unrolled sweep
     asm volatile("" : "+v"(bH), "+v"(bO), "+v"(bR4), "+v"(bR2), "+v"(bC4), "+v"(bDw), "+v"(bDr),
                  "+v"(bV), "+v"(bZero), "+v"(jlB));
+    // The next chunk's vectors travel during this chunk.  Issued behind the set-up above: on
+    // the tiles whose set-up reloads spilled registers, a reload behind the loads would wait
+    // for them.  (Unconditional, as in team A; the first iteration fetches the last chunk
+    // once more.)
+    stage_load(ck > 0 ? ck - 1 : 0);
     // R2 of chunk step sp (swept one super-step earlier): carry = f G + dS W^T ; dk slice.
     // Its dS is in exchange buffer `rd`.
     auto R2 = [&](int sp, int rd) __attribute__((always_inline)) {
