@@ -113,3 +113,26 @@ def test_null_alignment_workspace_errors():
     assert mb.m2rnn_fwd(d, A, A, A, A, A, None, A, None, None, None, check=False) == 1
     with pytest.raises(mb.M2RNNError):
         mb.m2rnn_fwd(d, None, A, A, A, A, None, A, None, None, big)
+
+
+def test_options_validation():
+    """m2rnn_fwd_opt / m2rnn_bwd_opt reject incomplete or misaligned option sets on the host."""
+    d = desc()
+    A = 0x1000
+    big = FakeBuf(0x100000, 1 << 40)
+    buf = lambda addr=0x2000: FakeBuf(addr, 64)
+    fwd = lambda o: mb.m2rnn_fwd_opt(d, o, A, A, A, A, A, None, A, None, None, big, check=False)
+    bwd = lambda o: mb.m2rnn_bwd_opt(d, o, A, A, A, A, A, None, None, A, None, A, A, A, A, A, None,
+                                     big, check=False)
+    # residual weight without its gradient buffer; gate parameters without beta / gradients
+    assert bwd(mb.make_opts(w_r=buf())) == 1
+    assert fwd(mb.make_opts(gate=(buf(), None))) == 1
+    assert bwd(mb.make_opts(gate=(buf(), buf()))) == 1
+    assert bwd(mb.make_opts(gate=(buf(), buf()), dgate=(buf(), None))) == 1
+    # misaligned option pointers
+    assert fwd(mb.make_opts(w_r=buf(0x2004))) == 4
+    assert bwd(mb.make_opts(w_r=buf(), dw_r=buf(0x2008))) == 4
+    assert fwd(mb.make_opts(gate=(buf(), buf(0x2002)))) == 4
+    # a bad descriptor is still reported first
+    assert mb.m2rnn_fwd_opt(desc(K=24), mb.make_opts(w_r=buf()), A, A, A, A, A, None, A, None,
+                            None, big, check=False) == 2
