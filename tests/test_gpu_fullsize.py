@@ -21,7 +21,7 @@ def _slice_heads(out, heads):
             res[n] = x[:, :, heads]
         elif n == "df":
             res[n] = x[:, :, heads]
-        elif n == "dW":
+        elif n in ("dW", "dw_r", "dalpha", "dbeta"):
             res[n] = x[heads]
         else:
             res[n] = x[:, heads]
@@ -95,3 +95,29 @@ def test_production_shape_all_heads_prefix():
     ref = gu.run_oracle(inp)
     errs = gu.compare(got, ref, gu.TOL[wl.io], label="P1 T=512")
     print("P1 T=512", {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)
+
+
+def test_full_size_options_C3():
+    """C3 at full size with the residual, the gate function and clipping in one call:
+    sampled head against the oracle run with the same options."""
+    from paper_2603_14360_amd.synth_inputs import make_gate_inputs, make_residual_weight
+    wl = WORKLOADS["C3"]
+    heads = [11]
+    print("case C3 options generating", flush=True)
+    inp = make_inputs(wl)
+    inp["w_r"] = make_residual_weight(wl)
+    inp["f"], inp["gate"] = make_gate_inputs(wl)
+    sub = select_heads(inp, heads)
+    sub["w_r"] = inp["w_r"][heads]
+    sub["gate"] = tuple(g[heads] for g in inp["gate"])
+    print("case C3 options oracle on heads", heads, flush=True)
+    free = gu.run_oracle(sub)
+    # a bound that is active for the sampled head (the other heads run with the same bound)
+    clip = 0.05 * float(max(np.abs(free["dH0"]).max(), np.abs(free["dW"]).max() / wl.T))
+    ref = gu.run_oracle(sub, grad_clip=clip)
+    assert gu.rel_err(free["dW"], ref["dW"]) > 1e-2
+    print("case C3 options gpu, clip", clip, flush=True)
+    got = gu.run_gpu(inp, wl.io, grad_clip=clip)
+    got = _slice_heads(got, heads)
+    errs = gu.compare(got, ref, gu.TOL[wl.io], label="C3 options")
+    print("C3 options", {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)
