@@ -298,7 +298,8 @@ __global__ void __launch_bounds__(TL::THREADS)
     // ---- lock-step schedule: one barrier per step, exchange buffer alternates.
     // (A ping-pong schedule -- the two row blocks of a workgroup half a step apart, two
     //  barriers per step, so that the waves sharing a SIMD alternate between operand fetch
-    //  and vector-ALU work -- was measured 10 % slower at B*N = 128, K = V = 64.)
+    //  and vector-ALU work -- was measured 15 % slower at B*N = 128, K = V = 64: the second
+    //  barrier costs more than the overlap returns.)
     for (int blk = 0; blk < nblk; ++blk) {
       const int t0 = blk * TB;
       const int len = (T - t0) < TB ? (T - t0) : TB;
