@@ -34,7 +34,7 @@ PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9  # lane-ops per second, packed fp32 not use
 # HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs of this script
 # (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same counter reads for the
 # --calib-copy-mib copy: x2.000 and x1.000).  Summary: profiles/c3_fwd_bwd_pmc_counters.txt.
-MEASURED_TRAFFIC_BYTES = {"C3": 439523 * 1024 * 2.000 + 670303 * 1024 * 1.000}
+MEASURED_TRAFFIC_BYTES = {"C3": 440049 * 1024 * 2.000 + 672730 * 1024 * 1.000}
 
 
 def alu_slots(kind):
