@@ -209,3 +209,55 @@ def test_single_step_decode_chain_bf16(K, V, Nqk):
     errs = {"y": gu.rel_err(y, ref["y"]), "HT": gu.rel_err(H.astype(np.float64), ref["HT"])}
     _report("decode K%d V%d" % (K, V), errs)
     assert errs["y"] <= gu.TOL["bf16"] and errs["HT"] <= gu.TOL["bf16"], errs
+
+
+def test_graph_capture_and_replay_bf16():
+    """The calls allocate nothing and synchronise nothing, so a forward + backward pair can
+    be captured into a HIP graph.  The graph is replayed three times on changing inputs, with
+    eager work and synchronisations in between, and every replay must equal the eager
+    result bit for bit (the kernels are deterministic)."""
+    import torch
+    from paper_2603_14360_amd import binding as mb
+    wl = _small("bf16", 2, 45, 4, 64, 64, seed=21)
+    sets = [gu.to_device(make_inputs(Workload("t", 2, 45, 4, 64, 64, "bf16", 21 + i, 0.125, 1.0,
+                                              use_H0=True, use_dHT=True)), "bf16") for i in range(3)]
+    names = ("q", "k", "v", "f", "W", "H0", "dy", "dHT")
+    static = {n: sets[0][n].clone() for n in names}
+    scan = mb.Scan(2, 45, 4, 64, 64, "bf16")
+
+    def run():
+        scan.fwd(static["q"], static["k"], static["v"], static["f"], static["W"], static["H0"])
+        scan.bwd(static["q"], static["k"], static["v"], static["f"], static["W"], static["H0"],
+                 static["dy"], static["dHT"])
+
+    print("case graph: eager references", flush=True)
+    eager = []
+    for st in sets:
+        for n in names:
+            static[n].copy_(st[n])
+        run()
+        torch.cuda.synchronize()
+        eager.append([x.clone() for x in (scan.y, scan.HT, scan.dq, scan.dk, scan.dv, scan.df,
+                                          scan.dW, scan.dH0)])
+    print("case graph: capture", flush=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run()
+    for i in (2, 0, 1):
+        print("case graph: replay on input set", i, flush=True)
+        for n in names:
+            static[n].copy_(sets[i][n])
+        for x in (scan.y, scan.dq, scan.dW):  # eager work between replays
+            x.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (scan.y, scan.HT, scan.dq, scan.dk, scan.dv, scan.df, scan.dW, scan.dH0)
+        for a, b in zip(got, eager[i]):
+            assert torch.equal(a, b)
