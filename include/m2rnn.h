@@ -94,7 +94,9 @@ size_t m2rnn_ckpt_bytes(const m2rnn_desc *desc);
 
 /* Bytes of scratch the forward (bwd = 0) or backward (bwd != 0) call needs for
  * partial sums across workgroups.  The backward figure includes room for
- * checkpoints, used only when bwd is called with ckpt == NULL.  May be 0. */
+ * checkpoints, used only when bwd is called with ckpt == NULL, and for the
+ * two-stage sums of the option gradients (dw_r, dgate_alpha, dgate_beta); the same
+ * size serves the plain and the _opt calls.  May be 0 for the forward. */
 size_t m2rnn_workspace_bytes(const m2rnn_desc *desc, int bwd);
 
 /*
