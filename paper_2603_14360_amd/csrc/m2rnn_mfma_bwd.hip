@@ -850,10 +850,27 @@ WsLayout bwd_ws_layout(int B, int T, int N, int Nqk, int K, int V, int P, int RB
   return w;
 }
 
+// T == 0: nothing is swept; dH0 = dHT (or 0) and dW = 0.  (The scan kernel is not launched:
+// its checkpoint prefetch has nothing valid to read, the caller may pass ckpt = NULL.)
+__global__ void bwd_empty_kernel(const float *__restrict__ dHT, float *__restrict__ dH0,
+                                 size_t n_state, float *__restrict__ dW, size_t n_dW) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n_dW; e += stride) dW[e] = 0.f;
+  if (dH0)
+    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n_state; e += stride)
+      dH0[e] = dHT ? dHT[e] : 0.f;
+}
+
 template <typename TL>
 hipError_t launch_bwd(const BwdArgs &a, hipStream_t s) {
   static_assert(OvLds<TL>::OK, "tile does not fit the two-team kernel");
   const int units = a.B * a.N;
+  if (a.T == 0) {
+    const size_t n_state = (size_t)units * a.K * a.V, n_dW = (size_t)a.N * a.V * a.V;
+    hipLaunchKernelGGL(bwd_empty_kernel, dim3(grid_for(n_state > n_dW ? n_state : n_dW, 256)),
+                       dim3(256), 0, s, a.dHT, a.dH0, n_state, a.dW, n_dW);
+    return hipGetLastError();
+  }
   const WsLayout w = bwd_ws_layout(a.B, a.T, a.N, a.Nqk, a.K, a.V, TL::P, TL::RB);
   BwdWs ws;
   ws.dvp = (float *)(a.ws + w.dvp);

@@ -261,3 +261,16 @@ def test_graph_capture_and_replay_bf16():
         got = (scan.y, scan.HT, scan.dq, scan.dk, scan.dv, scan.df, scan.dW, scan.dH0)
         for a, b in zip(got, eager[i]):
             assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_empty_sequence_without_checkpoint_buffer(io):
+    """T = 0 with ckpt = NULL: dH0 = dHT, dW = 0, H_T = H0, nothing else is touched."""
+    K = V = 32 if io == "f32" else 64
+    inp = make_inputs(_small(io, 2, 0, 2, K, V, seed=5))
+    print("case T=0, ckpt NULL", io, flush=True)
+    got = gu.run_gpu(inp, io, use_ckpt=False)
+    ref = gu.run_oracle(inp)
+    gu.compare(got, ref, gu.TOL[io], label="T=0 " + io)
+    assert np.array_equal(got["dH0"], inp["dHT"].astype(np.float64))
+    assert np.abs(got["dW"]).max() == 0.0
