@@ -187,6 +187,30 @@ m2rnn_status m2rnn_bwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
                            float *dW, float *dH0, void *workspace,
                            size_t workspace_bytes, void *hip_stream);
 
+/*
+ * m2rnn_fwd_opt for callers that cannot allocate device memory or size a workspace: code
+ * under HIP graph capture, tight serving loops (single-step or short-segment decode),
+ * harnesses that forbid hipMalloc.  It takes no workspace: the scratch the forward needs for
+ * its partial sums across workgroups is a device array inside the library, of
+ * M2RNN_STATIC_SCRATCH_BYTES bytes, which every GPU the library runs on holds until the
+ * process ends.  The call allocates nothing, frees nothing and synchronises nothing; it runs
+ * the same kernels as m2rnn_fwd_opt and gives the same bits.
+ *   - A descriptor whose m2rnn_workspace_bytes(desc, 0) exceeds M2RNN_STATIC_SCRATCH_BYTES is
+ *     rejected with M2RNN_ERR_WORKSPACE before anything is launched (e.g. B*T*N*V <= 2^19
+ *     at K = V = 64 with few states; shapes whose forward needs no scratch always pass).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ *     (different streams or threads) race; serialise them.  Nothing in the array needs to
+ *     start at zero: every part that is read in a call was written earlier in that call.
+ *   - The device address of the array is looked up on the first call on each device (with
+ *     that device current); M2RNN_ERR_HIP if the lookup fails.
+ * All other arguments, options and errors are those of m2rnn_fwd_opt.
+ */
+#define M2RNN_STATIC_SCRATCH_BYTES (8u << 20)
+m2rnn_status m2rnn_fwd_static(const m2rnn_desc *desc, const m2rnn_opts *opts, const void *q,
+                              const void *k, const void *v, const float *f, const void *W,
+                              const float *H0, void *y, float *HT, float *ckpt,
+                              void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

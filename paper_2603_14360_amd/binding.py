@@ -16,7 +16,8 @@ M2RNN_BF16 = 1
 
 EXPORTS = ("m2rnn_status_string", "m2rnn_default_chunk", "m2rnn_max_chunk",
            "m2rnn_ckpt_bytes", "m2rnn_workspace_bytes", "m2rnn_fwd", "m2rnn_bwd",
-           "m2rnn_fwd_opt", "m2rnn_bwd_opt")
+           "m2rnn_fwd_opt", "m2rnn_bwd_opt", "m2rnn_fwd_static")
+M2RNN_STATIC_SCRATCH_BYTES = 8 << 20
 
 
 class m2rnn_desc(ctypes.Structure):
@@ -72,6 +73,8 @@ def lib():
         L.m2rnn_fwd_opt.argtypes = [dp, op] + [vp] * 10 + [sz, vp]
         L.m2rnn_bwd_opt.restype = ctypes.c_int
         L.m2rnn_bwd_opt.argtypes = [dp, op] + [vp] * 16 + [sz, vp]
+        L.m2rnn_fwd_static.restype = ctypes.c_int
+        L.m2rnn_fwd_static.argtypes = [dp, op] + [vp] * 9 + [vp]
         _lib = L
     return _lib
 
@@ -151,6 +154,16 @@ def m2rnn_fwd_opt(desc, opts, q, k, v, f, W, H0, y, HT, ckpt, workspace, stream=
                              ctypes.c_void_p(stream or 0))
     if check and rc != 0:
         raise M2RNNError(rc, "m2rnn_fwd_opt")
+    return rc
+
+
+def m2rnn_fwd_static(desc, opts, q, k, v, f, W, H0, y, HT, ckpt, stream=None, check=True):
+    """m2rnn_fwd_opt on the library's own static scratch (no workspace argument)."""
+    rc = lib().m2rnn_fwd_static(ctypes.byref(desc), None if opts is None else ctypes.byref(opts),
+                                _ptr(q), _ptr(k), _ptr(v), _ptr(f), _ptr(W), _ptr(H0), _ptr(y),
+                                _ptr(HT), _ptr(ckpt), ctypes.c_void_p(stream or 0))
+    if check and rc != 0:
+        raise M2RNNError(rc, "m2rnn_fwd_static")
     return rc
 
 

@@ -3,6 +3,8 @@
 // method happens here.
 #include "../../include/m2rnn.h"
 
+#include <atomic>
+
 #include "m2rnn_kernels.hpp"
 
 using namespace m2rnn;
@@ -83,6 +85,58 @@ size_t family_ws(const m2rnn_desc *d, int C, int bwd) {
 
 bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
 
+// Library-owned scratch of m2rnn_fwd_static: one array per GPU, alive until the process ends.
+// The name below is a host-side handle only; the device address is looked up once per device
+// (each GPU holds its own copy at its own address) and only that address is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[M2RNN_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+void *static_scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // racing threads store the same value
+  }
+  return p;
+}
+
+m2rnn_status fwd_impl(const m2rnn_desc *desc, const m2rnn_opts *opts, const void *q,
+                      const void *k, const void *v, const float *f, const void *W,
+                      const float *H0, void *y, float *HT, float *ckpt, void *workspace,
+                      size_t workspace_bytes, void *hip_stream) {
+  m2rnn_status st = check_desc(desc);
+  if (st != M2RNN_OK) return st;
+  const int C = resolve_chunk(desc);
+  if (!C) return M2RNN_ERR_CHUNK;
+  const bool empty = desc->B == 0;
+  const bool steps = !empty && desc->T > 0;
+  if (!W) return M2RNN_ERR_NULL;
+  if (steps && (!q || !k || !v || !f || !y)) return M2RNN_ERR_NULL;
+  const void *w_r = opts ? opts->w_r : nullptr;
+  const float *ga = opts ? opts->gate_alpha : nullptr, *gb = ga ? opts->gate_beta : nullptr;
+  if (ga && !gb) return M2RNN_ERR_NULL;
+  const void *ptrs[] = {q, k, v, f, W, H0, y, HT, ckpt, workspace, w_r, ga, gb};
+  for (const void *p : ptrs)
+    if (misaligned(p)) return M2RNN_ERR_ALIGN;
+  const size_t need = family_ws(desc, C, 0);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return workspace ? M2RNN_ERR_WORKSPACE : M2RNN_ERR_NULL;
+
+  FwdArgs a;
+  a.B = desc->B; a.T = desc->T; a.N = desc->N; a.Nqk = desc->Nqk; a.K = desc->K; a.V = desc->V;
+  a.C = C; a.io = desc->io;
+  a.q = q; a.k = k; a.v = v; a.W = W; a.f = f; a.H0 = H0;
+  a.y = y; a.HT = HT; a.ckpt = ckpt; a.write_y = 1; a.ws = (char *)workspace;
+  a.w_r = w_r; a.gate_alpha = ga; a.gate_beta = gb;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const hipError_t e = run_fwd(desc, a, s);
+  return e == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -140,33 +194,27 @@ m2rnn_status m2rnn_fwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
                            const void *k, const void *v, const float *f, const void *W,
                            const float *H0, void *y, float *HT, float *ckpt, void *workspace,
                            size_t workspace_bytes, void *hip_stream) {
+  return fwd_impl(desc, opts, q, k, v, f, W, H0, y, HT, ckpt, workspace, workspace_bytes,
+                  hip_stream);
+}
+
+m2rnn_status m2rnn_fwd_static(const m2rnn_desc *desc, const m2rnn_opts *opts, const void *q,
+                              const void *k, const void *v, const float *f, const void *W,
+                              const float *H0, void *y, float *HT, float *ckpt,
+                              void *hip_stream) {
   m2rnn_status st = check_desc(desc);
   if (st != M2RNN_OK) return st;
   const int C = resolve_chunk(desc);
   if (!C) return M2RNN_ERR_CHUNK;
-  const bool empty = desc->B == 0;
-  const bool steps = !empty && desc->T > 0;
-  if (!W) return M2RNN_ERR_NULL;
-  if (steps && (!q || !k || !v || !f || !y)) return M2RNN_ERR_NULL;
-  const void *w_r = opts ? opts->w_r : nullptr;
-  const float *ga = opts ? opts->gate_alpha : nullptr, *gb = ga ? opts->gate_beta : nullptr;
-  if (ga && !gb) return M2RNN_ERR_NULL;
-  const void *ptrs[] = {q, k, v, f, W, H0, y, HT, ckpt, workspace, w_r, ga, gb};
-  for (const void *p : ptrs)
-    if (misaligned(p)) return M2RNN_ERR_ALIGN;
   const size_t need = family_ws(desc, C, 0);
-  if (need > 0 && (!workspace || workspace_bytes < need))
-    return workspace ? M2RNN_ERR_WORKSPACE : M2RNN_ERR_NULL;
-
-  FwdArgs a;
-  a.B = desc->B; a.T = desc->T; a.N = desc->N; a.Nqk = desc->Nqk; a.K = desc->K; a.V = desc->V;
-  a.C = C; a.io = desc->io;
-  a.q = q; a.k = k; a.v = v; a.W = W; a.f = f; a.H0 = H0;
-  a.y = y; a.HT = HT; a.ckpt = ckpt; a.write_y = 1; a.ws = (char *)workspace;
-  a.w_r = w_r; a.gate_alpha = ga; a.gate_beta = gb;
-  hipStream_t s = (hipStream_t)hip_stream;
-  const hipError_t e = run_fwd(desc, a, s);
-  return e == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
+  if (need > (size_t)M2RNN_STATIC_SCRATCH_BYTES) return M2RNN_ERR_WORKSPACE;
+  void *scratch_ptr = nullptr;
+  if (need > 0 && desc->B > 0 && desc->T > 0) {
+    scratch_ptr = static_scratch_of_current_device();
+    if (!scratch_ptr) return M2RNN_ERR_HIP;
+  }
+  return fwd_impl(desc, opts, q, k, v, f, W, H0, y, HT, ckpt, scratch_ptr,
+                  scratch_ptr ? (size_t)M2RNN_STATIC_SCRATCH_BYTES : 0, hip_stream);
 }
 
 m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k, const void *v,

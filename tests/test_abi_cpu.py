@@ -136,3 +136,17 @@ def test_options_validation():
     # a bad descriptor is still reported first
     assert mb.m2rnn_fwd_opt(desc(K=24), mb.make_opts(w_r=buf()), A, A, A, A, A, None, A, None,
                             None, big, check=False) == 2
+
+
+def test_static_scratch_entry_rejects_oversized_shapes_on_the_host():
+    """m2rnn_fwd_static takes no workspace; a forward whose partial sums do not fit the
+    library's static array is refused before any device is touched."""
+    big = mb.make_desc(8, 4096, 16, 64, 64, mb.M2RNN_BF16)
+    assert mb.m2rnn_workspace_bytes(big, 0) > mb.M2RNN_STATIC_SCRATCH_BYTES
+    buf = FakeBuf(1 << 20, 1 << 30)
+    args = [buf] * 5 + [None, buf, None, None]
+    assert mb.m2rnn_fwd_static(big, None, *args, check=False) == 5
+    assert mb.m2rnn_fwd_static(mb.make_desc(1, 8, 2, 24, 64, mb.M2RNN_BF16), None, *args,
+                               check=False) == 2
+    text = open(os.path.join(ROOT, "include", "m2rnn.h")).read()
+    assert "#define M2RNN_STATIC_SCRATCH_BYTES (8u << 20)" in text
