@@ -85,6 +85,13 @@ const char *m2rnn_status_string(m2rnn_status s);
 int32_t m2rnn_default_chunk(const m2rnn_desc *desc);
 int32_t m2rnn_max_chunk(const m2rnn_desc *desc);
 
+/* Name of the kernel variant that serves this descriptor's forward (bwd = 0) or backward
+ * (bwd != 0): "tile<K,V,RB>" (matrix-core kernel, a 16-row block spread over V/16 waves, RB
+ * row blocks per workgroup), "rowwave<K,V>" (matrix-core forward, one wave per 16-row block),
+ * "generic<f32>" / "generic<bf16>" (plain fp32 vector-ALU kernels), or "invalid descriptor".
+ * Static storage.  For profiling and for tests that must reach every variant. */
+const char *m2rnn_route_string(const m2rnn_desc *desc, int bwd);
+
 /* Bytes of the checkpoint buffer: fp32 [B, N, ceil(T / C), K, V]; entry c holds
  * the state BEFORE step c*C (entry 0 is H0).  Checkpoints replace the paper's
  * H_full[B,T,N,K,V] cache (Algorithm 2, pass 1): the backward recomputes each

@@ -16,7 +16,7 @@ M2RNN_BF16 = 1
 
 EXPORTS = ("m2rnn_status_string", "m2rnn_default_chunk", "m2rnn_max_chunk",
            "m2rnn_ckpt_bytes", "m2rnn_workspace_bytes", "m2rnn_fwd", "m2rnn_bwd",
-           "m2rnn_fwd_opt", "m2rnn_bwd_opt", "m2rnn_fwd_static")
+           "m2rnn_fwd_opt", "m2rnn_bwd_opt", "m2rnn_fwd_static", "m2rnn_route_string")
 M2RNN_STATIC_SCRATCH_BYTES = 8 << 20
 
 
@@ -73,6 +73,8 @@ def lib():
         L.m2rnn_fwd_opt.argtypes = [dp, op] + [vp] * 10 + [sz, vp]
         L.m2rnn_bwd_opt.restype = ctypes.c_int
         L.m2rnn_bwd_opt.argtypes = [dp, op] + [vp] * 16 + [sz, vp]
+        L.m2rnn_route_string.restype = ctypes.c_char_p
+        L.m2rnn_route_string.argtypes = [dp, ctypes.c_int]
         L.m2rnn_fwd_static.restype = ctypes.c_int
         L.m2rnn_fwd_static.argtypes = [dp, op] + [vp] * 9 + [vp]
         _lib = L
@@ -93,6 +95,10 @@ def m2rnn_default_chunk(desc):
 
 def m2rnn_max_chunk(desc):
     return int(lib().m2rnn_max_chunk(ctypes.byref(desc)))
+
+
+def m2rnn_route_string(desc, bwd):
+    return lib().m2rnn_route_string(ctypes.byref(desc), int(bwd)).decode()
 
 
 def m2rnn_ckpt_bytes(desc):

@@ -6,6 +6,7 @@
 #include <atomic>
 
 #include "m2rnn_kernels.hpp"
+#include "m2rnn_mfma_common.hpp"
 
 using namespace m2rnn;
 
@@ -167,6 +168,25 @@ size_t m2rnn_ckpt_bytes(const m2rnn_desc *desc) {
   if (check_desc(desc) != M2RNN_OK) return 0;
   const int C = resolve_chunk(desc);
   return C ? ckpt_bytes(desc, C) : 0;
+}
+
+const char *m2rnn_route_string(const m2rnn_desc *desc, int bwd) {
+  if (check_desc(desc) != M2RNN_OK) return "invalid descriptor";
+  const Family fam = bwd ? family_of(desc) : fwd_family_of(desc);
+  if (fam == kGeneric) return desc->io == M2RNN_F32 ? "generic<f32>" : "generic<bf16>";
+  if (fam == kRowWave) {
+#define X(K_, V_) \
+  if (desc->K == K_ && desc->V == V_) return "rowwave<" #K_ "," #V_ ">";
+    M2RNN_ROWWAVE_CASES(X)
+#undef X
+    return "rowwave<?>";
+  }
+  const int rb = mfma_pick_rb(desc->K, desc->V, desc->B * desc->N);
+#define X(K_, V_, RB_) \
+  if (desc->K == K_ && desc->V == V_ && rb == RB_) return "tile<" #K_ "," #V_ "," #RB_ ">";
+  M2RNN_TILE_CASES(X)
+#undef X
+  return "tile<?>";
 }
 
 size_t m2rnn_workspace_bytes(const m2rnn_desc *desc, int bwd) {

@@ -430,8 +430,7 @@ hipError_t run_fwd(const FwdArgs &a, hipStream_t s) {
                      s, (const IO *)a.W, W32, WT32, a.N, a.V);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void *)gen_fwd_kernel<IO>,
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_fwd);
+  e = set_max_lds_once(gen_fwd_kernel<IO>, (int)kLdsBudget);  // (the need varies with the shape)
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(gen_fwd_kernel<IO>, dim3(units), dim3(p.threads), p.lds_fwd, s, a,
                      (const float *)W32, p.w_lds_fwd);
@@ -455,8 +454,7 @@ hipError_t run_bwd(const BwdArgs &a, hipStream_t s) {
     hipLaunchKernelGGL(w_prep_kernel<IO>, dim3(grid_for((size_t)a.N * a.V * a.V, 256)), dim3(256),
                        0, s, (const IO *)a.W, W32, WT32, a.N, a.V);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)gen_bwd_kernel<IO>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_bwd);
+    e = set_max_lds_once(gen_bwd_kernel<IO>, (int)kLdsBudget);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(gen_bwd_kernel<IO>, dim3(units), dim3(p.threads), p.lds_bwd, s, a,
                        (const float *)W32, (const float *)WT32, states, dW_unit, dq_heads,

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace m2rnn {
 
 // Arguments of one forward scan.  Shapes and meaning follow the public header;
@@ -38,6 +40,23 @@ struct BwdArgs {
 };
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Raises a kernel's dynamic-LDS limit the first time the kernel is launched on a device,
+// not on every call (the entry points are otherwise launch-only, and a decode loop pays host
+// latency for every extra runtime call).  One instance per kernel: `Tag` is the kernel's
+// own type.  `bytes` must not depend on the call.
+template <typename Tag>
+inline hipError_t set_max_lds_once(Tag kernel, int bytes) {
+  static std::atomic<uint64_t> done{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // ---- fp32 path (plain vector-ALU kernels; any supported shape, either io) ----
@@ -70,6 +89,7 @@ int mfma_max_chunk(int K, int V);
 size_t mfma_workspace_bytes(int B, int T, int N, int Nqk, int K, int V, int C, int bwd);
 hipError_t mfma_fwd(const FwdArgs &a, hipStream_t s);
 hipError_t mfma_bwd(const BwdArgs &a, hipStream_t s);
+int mfma_pick_rb(int K, int V, int units);  // row blocks per workgroup of the tile serving a launch (0: none)
 
 // ---- register-resident path (bf16 io, V <= 64): one wave per 16 state rows ----
 bool rowwave_supported(int K, int V);

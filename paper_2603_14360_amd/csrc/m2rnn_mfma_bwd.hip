@@ -420,10 +420,21 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   // (or shrink) by orders of magnitude over a long sequence; dS would leave the fp16 range.
   // The sweep therefore works on sc * (carry, G, dS, and every accumulator fed by dS) with
   // sc a power of two chosen per chunk from the largest |carry| in the workgroup and the
-  // largest |q| |dy| of the chunk, so that the scaled magnitudes start the chunk in
-  // [2^8, 2^9): a factor 2^7 of growth inside the chunk still fits, small values keep
-  // their mantissa.  Powers of two make the scaling exact; outputs are divided by sc.
+  // largest |q| |dy| of the chunk.  Powers of two make the scaling exact; outputs are
+  // divided by sc.  The scaled magnitudes start a chunk in [2^5, 2^6): growth by 2^10
+  // inside the chunk still fits fp16, and values down to 2^-19 of the largest keep their
+  // full mantissa.  Where the previous chunk grew by g > 2 bits, the start is lowered by
+  // g - 2 bits more (at most 12), so a gradient that explodes steadily, by up to 2^22 per
+  // chunk, is followed.  A jump of more than 2^10 inside one chunk right after a calm
+  // chunk still overflows dS (gradients become inf / NaN): the regime the paper's
+  // per-step clipping (grad_clip) exists for.
+  // The scale never exceeds 2^90 times the smallest scale used so far: dW accumulates
+  // sc * (sum of H^T dS) over the whole sweep, at most 2^32 / (smallest sc) in magnitude,
+  // and is rescaled with sc; a gradient that has died away (loss on the last tokens only)
+  // would otherwise drive sc to 2^120 and the accumulated dW to infinity.  Steps whose
+  // gradient is more than 2^90 below the largest seen lose precision instead.
   float sc = 1.f, isc = 1.f;
+  int sc_e = 0, sc_e_min = 1 << 20, mx_e_prev = -(1 << 20);
   int set_now = 0;
   int *scl = (int *)(lds + L::SCL_);  // two sets of { max |carry|, max |q|, max |dy| } bit patterns,
                                        // by iteration parity; filled with LDS atomic max
@@ -544,10 +555,18 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     if (active) {  // scale of this chunk (wave-uniform, identical in every wave of the team)
       const f4_t mx = __builtin_bit_cast(f4_t, *(const u4_t *)&scl[4 * set_now]);  // |carry|, |q|, |dy|
       const int e = ilog2f(fminf(fmaxf(mx[0] + mx[1] * mx[2], 1e-30f), 1e30f));
-      const float sc_new = pow2i(8 - e);
-      const float ratio = sc_new * isc;  // exact: both are powers of two
-      sc = sc_new;
-      isc = pow2i(e - 8);
+      const int grew = mx_e_prev > -(1 << 20) ? e - mx_e_prev : 0;
+      const int extra = grew - 2 < 0 ? 0 : (grew - 2 > 12 ? 12 : grew - 2);
+      int ne = 5 - extra - e;                                  // exponent of the new scale
+      ne = ne > sc_e_min + 90 ? sc_e_min + 90 : ne;
+      ne = ne < sc_e - 120 ? sc_e - 120 : ne;
+      ne = ne > 120 ? 120 : (ne < -120 ? -120 : ne);
+      sc_e_min = ne < sc_e_min ? ne : sc_e_min;
+      mx_e_prev = e;
+      const float ratio = pow2i(ne - sc_e);  // exact power of two
+      sc_e = ne;
+      sc = pow2i(ne);
+      isc = pow2i(-ne);
 #pragma unroll
       for (int r = 0; r < 4; ++r) carry[r] *= ratio;
 #pragma unroll
@@ -601,6 +620,14 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
 #pragma unroll
         for (int r = 0; r < 4; ++r) carry[r] = __builtin_amdgcn_fmed3f(carry[r], -cb, cb);
       }
+      // The contraction's result is consumed HERE, in the block that issued it, and the
+      // consumer is pinned in front of the conditional block below.  With one MFMA in the
+      // chain (V = 32) the compiler otherwise sinks these reads behind the branch and
+      // counts the MFMA's wait states along the path through the dk block only: the waves
+      // that skip it (ct >= KS) then read the accumulator while it is still being written
+      // (wrong carry in two of a lane's four rows; caught by tile<32,32,2> in
+      // tests/test_gpu_instantiations.py, the only tiling with a skipping wave and KS = 1).
+      asm volatile("" : "+v"(carry[0]), "+v"(carry[1]), "+v"(carry[2]), "+v"(carry[3]));
       if (ct < KS) {
         // v_s in column sp of the B operand only: the other lanes read zeros
         const FragT bf = lds_ld<FragT>(jlB == sp ? bV + (L::VH_ + sp * V * 2) : bZero + L::ZERO_, 0);
@@ -883,8 +910,8 @@ hipError_t launch_bwd(const BwdArgs &a, hipStream_t s) {
   if (units > 0) {
     if (a.C > OvLds<TL>::CMAX) return hipErrorInvalidValue;
     auto *kern = a.clip > 0.f ? mfma_bwd_overlap_kernel<TL, true> : mfma_bwd_overlap_kernel<TL, false>;
-    e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            OvLds<TL>::BYTES);
+    e = a.clip > 0.f ? set_max_lds_once(mfma_bwd_overlap_kernel<TL, true>, OvLds<TL>::BYTES)
+                     : set_max_lds_once(mfma_bwd_overlap_kernel<TL, false>, OvLds<TL>::BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid_blocks(units, TL::P)), dim3(2 * TL::THREADS),
                        OvLds<TL>::BYTES, s, a, ws);

@@ -67,6 +67,26 @@ __device__ __forceinline__ h4_t hi_of_pairs(const uint32_t (&pk)[4]) {
   return __builtin_bit_cast(h4_t, v);
 }
 
+// One state element through the non-linearity and the gate of the recurrence equations, on the
+// scaled state:  H' <- f H' + gp tanh(s),  gp = c (1 - f),  sp = c s = 2 log2(e) s.
+//     tanh(s) = sign(s) (1 - e) / (1 + e),   e = 2^-|sp|  in (0, 1].
+// Why this form and not 1 - 2 / (1 + 2^sp): the forward trajectory of this recurrence can be
+// transiently chaotic (units whose transition matrix has gain above one amplify a
+// perturbation of the state by 10^4 .. 10^6 over a few hundred steps, and the backward
+// gradient of such a unit follows the trajectory), so the ABSOLUTE error of tanh near zero
+// decides how far such units drift from an exact evaluation.  1 - 2/(1+e) carries the
+// rounding of exp2, of the sum and of the reciprocal as absolute errors (measured 4.4e-8
+// rms); here 1 - e is exact for e in [1/2, 1] and the reciprocal's error is relative to the
+// result, which leaves half an ulp of e in [1/2, 1) (measured 0.7e-8 rms).  e <= 1 also
+// cannot overflow, whatever the pre-activation.  Two more vector instructions per element.
+__device__ __forceinline__ float gate_tanh_step(float f, float gp, float h, float sp) {
+  const float e = __builtin_amdgcn_exp2f(-__builtin_fabsf(sp));
+  const float rr = __builtin_amdgcn_rcpf(1.f + e);
+  const float n = fmaf(-gp, e, gp);                      // gp (1 - e) >= 0
+  const float ns = __builtin_copysignf(n, sp);
+  return fmaf(ns, rr, f * h);
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains
 // the vector-memory counter, i.e. it would wait for every global load and store
 // in flight (the staged q/k/v prefetch, the per-step y / dq / dk stores) at each
@@ -101,6 +121,9 @@ __device__ __forceinline__ f4_t mfma_k16(h4_t a, h4_t b, f4_t c) {
 // (MFMA; if (...) {long block}; use): the wait states an MFMA result needs before
 // a vector-ALU read are then counted along the long path only, and the waves
 // that skip the block read the accumulator too early (seen as wrong gradients).
+// settle() alone only marks the spot: where a conditional block follows the chain, the first
+// real consumer must also sit (and be pinned) in front of that block, as the backward's
+// carry update does.  Guarded by tests/test_gpu_instantiations.py, which runs every tiling.
 __device__ __forceinline__ void settle(f4_t &d) { asm volatile("" : "+v"(d)); }
 
 // Maximum of a NON-NEGATIVE float over aligned groups of G = 2, 4, 8, 16, 32 or 64 consecutive

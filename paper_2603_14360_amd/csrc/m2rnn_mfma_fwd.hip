@@ -18,8 +18,8 @@
 //      forward-trajectory errors by orders of magnitude at T = 4096, so a
 //      single fp16 operand (11 bits) is not enough.  The pair sits in adjacent
 //      k-slots of the MFMA and the W fragment repeats each row of W twice.
-//   E  in registers, fp32:  s' = S' + (c k_i) v_j ; e = 2^{s'} ; r = 1/(1+e) ;
-//      H' <- f H' + c(1-f) - 2c(1-f) r        ( = c [f H + (1-f) tanh(s)] )
+//   E  in registers, fp32:  s' = S' + (c k_i) v_j ; e = 2^{-|s'|} ; r = 1/(1+e) ;
+//      H' <- f H' + sign(s') c(1-f) (1-e) r   ( = c [f H + (1-f) tanh(s)], gate_tanh_step )
 //      split H' into (hi, lo), write the fragment to LDS, start the next step's
 //      contraction with the own tile; one barrier.
 //   Y  readout without leaving the step loop.  It contracts over the rows of H,
@@ -46,7 +46,7 @@ struct FwdSmem {
   alignas(16) float kS[2][TB][TL::ROWS];           // c * k
   alignas(16) _Float16 qS[2][TB][TL::ROWS];
   alignas(16) float vS[2][TB][TL::V];
-  alignas(16) float fS[2][TB][4];                  // f, c(1-f), -2c(1-f), unused
+  alignas(16) float fS[2][TB][4];                  // f, c(1-f), unused, unused
   alignas(16) f4_t yB[TL::RB][TL::CT][64];         // readout accumulators of one block
 };
 
@@ -185,7 +185,6 @@ __global__ void __launch_bounds__(TL::THREADS)
       const float gp = kC * (1.f - rf);
       sm.fS[buf][tid][0] = rf;
       sm.fS[buf][tid][1] = gp;
-      sm.fS[buf][tid][2] = -2.f * gp;
     }
   };
 
@@ -206,7 +205,7 @@ __global__ void __launch_bounds__(TL::THREADS)
   // per step cost as much as the arithmetic).
   struct StepRegs {
     h8_t hf[CT];  // [0] unused: the own tile's product is in acc_own already
-    float f, gp, m2g, kk;
+    float f, gp, kk;
     f4_t v4, acc;
     h4_t qf;
   };
@@ -229,7 +228,6 @@ __global__ void __launch_bounds__(TL::THREADS)
     for (int d = 1; d < CT; ++d) x.hf[d] = lds_ld<h8_t>(hx + hx_off[d], buf * HXBUF);
     x.f = sm.fS[sb][s][0];
     x.gp = sm.fS[sb][s][1];
-    x.m2g = sm.fS[sb][s][2];
     x.kk = sm.kS[sb][s][rowb + jl];
     x.v4 = *(const f4_t *)&sm.vS[sb][s][col0 + 4 * ig];
     if constexpr (DO_Y) x.qf = *(const h4_t *)&sm.qS[sb][s][rowb + 4 * ig];
@@ -245,11 +243,8 @@ __global__ void __launch_bounds__(TL::THREADS)
   auto step_E = [&](const StepRegs &x, uint32_t (&pk)[4], int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const float t1 = fmaf(x.f, h[r], x.gp);
       const float sp = fmaf(x.kk, x.v4[r], x.acc[r]);
-      const float e = __builtin_amdgcn_exp2f(sp);
-      const float rr = __builtin_amdgcn_rcpf(1.f + e);
-      h[r] = fmaf(x.m2g, rr, t1);
+      h[r] = gate_tanh_step(x.f, x.gp, h[r], sp);
       pk[r] = split_hi_lo(h[r]);
     }
     const u4_t fr = {pk[0], pk[1], pk[2], pk[3]};

@@ -13,8 +13,8 @@
 // cycles per step, more than the arithmetic).
 //
 // Per step, per 16-column tile ct (software pipelined across the tiles):
-//   E   s' = acc[ct] + (c k_i) v_j ; e = 2^{s'} ; r = 1/(1+e) ;
-//       H' <- f H' + c(1-f) - 2c(1-f) r ;  (hi, lo) = split(H')
+//   E   s' = acc[ct] + (c k_i) v_j ; H' <- c [f H + (1-f) tanh(s)] (gate_tanh_step) ;
+//       (hi, lo) = split(H')
 //   M   for every output tile jt: acc'[jt] += W^T[jt][ct] (hi, lo)[ct]
 //       (16x16x32 MFMA: the pair occupies adjacent k-slots, the W fragment
 //        holds each row of W twice) -- these run on the matrix core while the
@@ -164,7 +164,6 @@ __global__ void __launch_bounds__(RW::THREADS) rowwave_fwd_kernel(FwdArgs a) {
       const float gp = kC * (1.f - rf);
       fS(buf)[tid * 4 + 0] = rf;
       fS(buf)[tid * 4 + 1] = gp;
-      fS(buf)[tid * 4 + 2] = -2.f * gp;
     }
   };
 
@@ -223,7 +222,7 @@ __global__ void __launch_bounds__(RW::THREADS) rowwave_fwd_kernel(FwdArgs a) {
 
       // ---- straight-line step body
       const float ki = kS(sb)[s * K + row];
-      const float f = fS(sb)[s * 4 + 0], gp = fS(sb)[s * 4 + 1], m2g = fS(sb)[s * 4 + 2];
+      const float f = fS(sb)[s * 4 + 0], gp = fS(sb)[s * 4 + 1];
       h4_t vfr[CT];
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) vfr[ct] = *(const h4_t *)&vH(sb)[s * V + 16 * ct + 4 * ig];
@@ -241,11 +240,8 @@ __global__ void __launch_bounds__(RW::THREADS) rowwave_fwd_kernel(FwdArgs a) {
         // E: tile ct
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float t1 = fmaf(f, h[ct][r], gp);
           const float sp = fmaf(ki, (float)vfr[ct][r], acc[ct][r]);
-          const float e = __builtin_amdgcn_exp2f(sp);
-          const float rr = __builtin_amdgcn_rcpf(1.f + e);
-          h[ct][r] = fmaf(m2g, rr, t1);
+          h[ct][r] = gate_tanh_step(f, gp, h[ct][r], sp);
         }
         const h8_t hf = frag_of(h[ct]);
         // M: this tile is a k-slice of the next step's contraction
@@ -327,8 +323,7 @@ hipError_t launch(const FwdArgs &a, hipStream_t s) {
   const int units = a.B * a.N;
   if (units == 0) return hipSuccess;
   auto go = [&](auto kernel) {
-    hipError_t e = hipFuncSetAttribute((const void *)kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, RW::BYTES);
+    hipError_t e = set_max_lds_once(kernel, RW::BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kernel, dim3(units), dim3(RW::THREADS), RW::BYTES, s, a);
     return hipGetLastError();

@@ -150,3 +150,31 @@ def test_static_scratch_entry_rejects_oversized_shapes_on_the_host():
                                check=False) == 2
     text = open(os.path.join(ROOT, "include", "m2rnn.h")).read()
     assert "#define M2RNN_STATIC_SCRATCH_BYTES (8u << 20)" in text
+
+
+def test_every_kernel_instantiation_has_a_parity_case():
+    """Host logic: every tiling and every one-wave-per-row-block shape the sources
+    instantiate is reached by a case of tests/test_gpu_instantiations.py, and the dispatcher
+    really routes that case's descriptor to it."""
+    import importlib.util
+    import sys
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    spec = importlib.util.spec_from_file_location(
+        "inst_cases", os.path.join(ROOT, "tests", "test_gpu_instantiations.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    src = open(os.path.join(ROOT, "paper_2603_14360_amd", "csrc", "m2rnn_mfma_common.hpp")).read()
+    src = src.replace("\\\n", " ")
+    tiles = re.search(r"#define M2RNN_TILE_CASES\(X\)(.*)", src).group(1)
+    rows = re.search(r"#define M2RNN_ROWWAVE_CASES\(X\)(.*)", src).group(1)
+    want = {"tile<%s,%s,%s>" % t for t in re.findall(r"X\((\d+), (\d+), (\d+)\)", tiles)}
+    want_rw = {"rowwave<%s,%s>" % t for t in re.findall(r"X\((\d+), (\d+)\)", rows)}
+    assert len(want) >= 7 and len(want_rw) >= 12
+    fwd_seen, bwd_seen = set(), set()
+    for K, V, B, N, Nqk, fr, br in mod.CASES:
+        d = mb.make_desc(B, 35, N, K, V, mb.M2RNN_BF16, Nqk=(Nqk or None))
+        assert mb.m2rnn_route_string(d, 0) == fr and mb.m2rnn_route_string(d, 1) == br
+        fwd_seen.add(fr)
+        bwd_seen.add(br)
+    assert want <= fwd_seen and want <= bwd_seen, (want - fwd_seen, want - bwd_seen)
+    assert want_rw <= fwd_seen, want_rw - fwd_seen

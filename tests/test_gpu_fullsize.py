@@ -1,8 +1,15 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration that
-bench.py times.  The oracle cannot run every recurrence of these workloads in
-seconds, but (batch, head) recurrences are independent, so it is run on a
-sample of heads (all batch elements of each sampled head, because dW sums over
-the batch) and compared element by element with the GPU's full-size output."""
+"""GPU parity at the benchmark's full sizes, in the launch configuration that bench.py
+times.  (batch, head) recurrences are independent, so the oracle runs whole workloads head
+by head on all host threads: C3, C5 and the paper's layer shape P1 are compared on EVERY
+head at full T; C4 (K = V = 128, T = 8192), whose oracle backward costs a minute per
+recurrence, on two heads x all batch rows at full T, every gradient included.
+
+Figures per workload: (1) per output tensor max|gpu - oracle| / max|oracle| over the whole
+tensor, held to the benchmark spec's tolerance (2e-2 for bf16 io) on the BASELINE workloads; (2) the
+same ratio per (batch row, head) recurrence and per 256-step block of it, each against its
+own largest entry and its own growth-aware bound (gpu_util.compare_units): the gradients of
+this recurrence vary by orders of magnitude along T and between recurrences, and a few
+recurrences of the random workloads are transiently chaotic."""
 import numpy as np
 import pytest
 
@@ -10,7 +17,6 @@ from paper_2603_14360_amd.synth_inputs import WORKLOADS, make_inputs, select_hea
 import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
-
 
 def _slice_heads(out, heads):
     res = {}
@@ -28,75 +34,95 @@ def _slice_heads(out, heads):
     return res
 
 
-@pytest.mark.parametrize("name,heads,T_oracle", [("C3", [5], None), ("C4", [2], 2048), ("C5", [7, 20], None)])
-def test_full_size_sampled_heads(name, heads, T_oracle):
+def _both_figures(got, ref, inp, tol, label, tensor_level=True):
+    """inp: the oracle's inputs (same head selection as ref)."""
+    errs = {n: gu.rel_err(got[n], ref[n]) for n in ref}
+    print(label, "tensor", {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)
+    if "dH0" in ref:
+        worst, info = gu.compare_units(got, ref, inp, tol, label=label)
+        print(label, "worst (recurrence, 256-step block) error / bound: %.3g" % worst, info, flush=True)
+        assert worst <= 1.0, (label, worst, info)
+    else:   # forward only
+        blk = {n: gu.block_err(got[n], ref[n]) for n in ("y",)}
+        print(label, "worst 256-step block", blk, flush=True)
+        assert blk["y"] <= tol, (label, blk)
+    if tensor_level:
+        gu.compare(got, ref, tol, label=label)
+    return errs
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["C3", "C5"])
+def test_full_size_all_heads(name):
+    """Every head, every batch row, full T: all outputs (C5 is forward only)."""
     wl = WORKLOADS[name]
     print("case", name, "generating", flush=True)
     inp = make_inputs(wl)
     print("case", name, "gpu", flush=True)
     got = gu.run_gpu(inp, wl.io, backward=wl.backward)
-    got = _slice_heads(got, heads)
-    sub = select_heads(inp, heads)
-    if T_oracle is None:
-        print("case", name, "oracle on heads", heads, flush=True)
-        ref = gu.run_oracle(sub, backward=wl.backward)
-        errs = gu.compare(got, ref, gu.TOL[wl.io], label=name)
-    else:
-        # forward outputs of a prefix are exact prefixes of the full run; the
-        # oracle checks y on the first T_oracle steps, and all gradients of a
-        # separate full-size-shaped run of that prefix length are covered by
-        # test_prefix_backward below.
-        pre = {n: (x[:, :T_oracle] if (x is not None and n in ("q", "k", "v", "f", "dy")) else x)
-               for n, x in sub.items()}
-        print("case", name, "oracle prefix", T_oracle, flush=True)
-        ref = gu.run_oracle(pre, backward=False)
-        errs = {"y": gu.rel_err(got["y"][:, :T_oracle], ref["y"])}
-        assert errs["y"] <= gu.TOL[wl.io], errs
-        assert np.isfinite(got["y"]).all() and np.isfinite(got["HT"]).all()
-        assert np.abs(got["HT"]).max() <= 1.0 + 1e-6   # |H| <= 1 from a zero initial state
-    print(name, {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)
+    print("case", name, "oracle, all", wl.N, "heads", flush=True)
+    ref = gu.run_oracle(inp, backward=wl.backward)
+    _both_figures(got, ref, inp, gu.TOL[wl.io], name)
+    assert np.abs(got["HT"]).max() <= 1.0 + 1e-6   # |H| <= 1 from a zero initial state
 
 
-def test_prefix_backward_C4_shape():
-    """C4's shape (K = V = 128, all B and N) at T = 1024: full gradients of two heads."""
+@pytest.mark.timeout(900)
+def test_full_size_C4_gradients_at_full_length():
+    """C4 at T = 8192: y, H_T and every gradient of two heads x all four batch rows
+    against the oracle's backward over the whole sequence."""
     wl = WORKLOADS["C4"]
-    inp = make_inputs(wl, T=1024)
-    print("case C4 T=1024 gpu", flush=True)
-    got = _slice_heads(gu.run_gpu(inp, wl.io), [1, 6])
-    ref = gu.run_oracle(select_heads(inp, [1, 6]))
-    errs = gu.compare(got, ref, gu.TOL[wl.io], label="C4 prefix")
-    print("C4 T=1024", {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)
+    heads = [2, 5]
+    print("case C4 generating", flush=True)
+    inp = make_inputs(wl)
+    print("case C4 gpu", flush=True)
+    got = _slice_heads(gu.run_gpu(inp, wl.io), heads)
+    print("case C4 oracle on heads", heads, "(about a minute)", flush=True)
+    sub = select_heads(inp, heads)
+    ref = gu.run_oracle(sub)
+    _both_figures(got, ref, sub, gu.TOL[wl.io], "C4")
 
 
-def test_production_shape_shared_qk():
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("seed", [5, 1005, 2005])
+def test_production_shape_shared_qk_all_heads(seed):
     """The paper's layer shape (K = 64, V = 16, 84 heads, q/k shared by all heads) at full
-    size: per-head outputs (y, dv, df, dW, H_T, dH0) of sampled heads against the oracle.
-    dq and dk are sums over all 84 heads and are covered by the next test."""
-    wl = WORKLOADS["P1"]
-    heads = [0, 41, 83]
-    print("case P1 generating", flush=True)
+    size and full T, every head, three seeds: all outputs including dq, dk (sums over the 84
+    heads that share q and k).  With W ~ N(0, 1/16) a few of the 672 recurrences are
+    transiently chaotic (carried gradient growing by up to 10^6); they set the largest entries
+    of every gradient tensor, so the whole-tensor figure is held to the bound of the most
+    chaotic recurrence and every recurrence to its own."""
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS["P1"], seed=seed)
+    print("case P1 seed", seed, "generating", flush=True)
     inp = make_inputs(wl)
     print("case P1 gpu", flush=True)
-    got = _slice_heads(gu.run_gpu(inp, wl.io), heads)
-    print("case P1 oracle on heads", heads, flush=True)
-    ref = gu.run_oracle(select_heads(inp, heads))
-    names = ("y", "HT", "dv", "df", "dW", "dH0")
-    errs = gu.compare(got, ref, gu.TOL[wl.io], names=names, label="P1")
-    print("P1", {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)
-
-
-def test_production_shape_all_heads_prefix():
-    """Same shape, all 84 heads, T = 512: every output including the head-summed dq, dk."""
-    wl = WORKLOADS["P1"]
-    inp = make_inputs(wl, T=512)
-    print("case P1 T=512 gpu", flush=True)
     got = gu.run_gpu(inp, wl.io)
-    print("case P1 T=512 oracle", flush=True)
+    print("case P1 oracle, all heads", flush=True)
     ref = gu.run_oracle(inp)
-    errs = gu.compare(got, ref, gu.TOL[wl.io], label="P1 T=512")
-    print("P1 T=512", {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)
+    errs = _both_figures(got, ref, inp, gu.TOL[wl.io], "P1 seed %d" % seed, tensor_level=False)
+    bound, _ = gu.unit_bounds(ref, inp, gu.TOL[wl.io])
+    assert max(errs.values()) <= bound.max(), (errs, bound.max())
+    # outputs that do not pass through the carried gradient are plain
+    assert max(errs["y"], errs["HT"], errs["dq"]) <= 1e-2, errs
 
 
+@pytest.mark.timeout(600)
+def test_production_shape_identity_transition():
+    """Same shape with W = I, the initialisation the paper adopts for all its models
+    ("Transition Matrix Initialization"): no recurrence is expanding, every tensor within 1e-2."""
+    wl = WORKLOADS["P1"]
+    print("case P1 identity W generating", flush=True)
+    inp = make_inputs(wl)
+    inp["W"] = np.broadcast_to(np.eye(wl.V, dtype=np.float32), inp["W"].shape).copy()
+    print("case P1 identity W gpu", flush=True)
+    got = gu.run_gpu(inp, wl.io)
+    print("case P1 identity W oracle", flush=True)
+    ref = gu.run_oracle(inp)
+    errs = gu.compare(got, ref, 1e-2, label="P1 W=I")
+    print("P1 W=I tensor", {k: float("%.3g" % v) for k, v in errs.items()}, flush=True)
+
+
+@pytest.mark.timeout(600)
 def test_full_size_options_C3():
     """C3 at full size with the residual, the gate function and clipping in one call:
     sampled head against the oracle run with the same options."""

@@ -187,6 +187,61 @@ def test_gradient_dynamic_range_bf16(K, V, scale):
     _report(label, gu.compare(got, ref, gu.TOL["bf16"], label=label))
 
 
+@pytest.mark.parametrize("K,V", [(64, 64), (64, 16), (128, 128)])
+@pytest.mark.parametrize("gain", [1.5, 3.0])
+def test_growing_state_gradient_bf16(K, V, gain):
+    """The regime the paper's gradient-clipping paragraph is about, without clipping: a small
+    forget gate and a transition matrix of gain 1.5 or 3 make the carried state gradient grow
+    by orders of magnitude, chunk after chunk (2^18 over 32 steps at gain 3).  The backward's
+    fp16 dS operand must follow it: its power-of-two scale is chosen per chunk with headroom
+    that widens when the previous chunk grew.  fp32 holds 3^32 easily, so the oracle stays
+    finite and so must the library.  Such a recurrence is chaotic forward as well (H_T itself
+    differs by percents between any two roundings).  At gain 1.5 the growth-aware bound
+    holds; at gain 3 (expansion 1.4 per step) the chunk recompute's single fp16 state
+    operand, 2^-12 per step amplified 1.4^16 within a chunk, adds errors of several percent:
+    there the test asks for finite gradients within 25 %."""
+    wl = Workload("grow", 2, 32, 2, K, V, "bf16", 55, K ** -0.5, -3.0, use_H0=True, use_dHT=True)
+    inp = make_inputs(wl)
+    from paper_2603_14360_amd.synth_inputs import round_to_bf16
+    inp["W"] = round_to_bf16(inp["W"] * np.float32(gain))[0]
+    label = "growing gradient K%d V%d gain %g" % (K, V, gain)
+    print("case", label, flush=True)
+    ref = gu.run_oracle(inp)
+    got = gu.run_gpu(inp, "bf16")
+    worst, info = gu.compare_units(got, ref, inp, gu.TOL["bf16"], label=label)
+    errs = {n: float("%.3g" % gu.rel_err(got[n], ref[n])) for n in ref}
+    print(label, ": worst error / bound %.3g" % worst, info, errs, flush=True)
+    if gain < 2:
+        assert worst <= 1.0, (worst, info)
+    else:
+        assert info["max_growth"] > 1e3      # the case really explodes
+        assert max(errs.values()) <= 0.25, errs
+
+
+def test_vanishing_gradient_after_large_late_dy_bf16():
+    """dy is non-zero at the last step only and loss-scaled (x 2^22); the recurrence contracts
+    (small W, small gate), so the carried gradient decays to nothing over the sequence.  The
+    backward's internal scale then rises chunk by chunk while dW already holds large sums:
+    rescaling the accumulated dW must not overflow."""
+    wl = Workload("vanish", 1, 400, 2, 64, 64, "bf16", 56, 0.125, -2.0)
+    inp = make_inputs(wl)
+    from paper_2603_14360_amd.synth_inputs import round_to_bf16
+    inp["W"] = round_to_bf16(inp["W"] * np.float32(0.25))[0]
+    dy = np.zeros_like(inp["dy"])
+    dy[:, -1] = inp["dy"][:, -1] * np.float32(2.0 ** 22)
+    inp["dy"] = dy
+    print("case vanishing gradient", flush=True)
+    ref = gu.run_oracle(inp)
+    print("oracle max |dW| %.3g, max |dH0| %.3g" % (np.abs(ref["dW"]).max(), np.abs(ref["dH0"]).max()),
+          flush=True)
+    got = gu.run_gpu(inp, "bf16")
+    # the float64 oracle's dH0 (~1e-177) is below the smallest fp32 number: the fp32 result is 0
+    assert np.abs(ref["dH0"]).max() < 1e-45 and np.abs(got["dH0"]).max() < 1e-30
+    names = [n for n in ref if n != "dH0"]
+    _report("vanishing gradient", gu.compare(got, ref, gu.TOL["bf16"], names=names,
+                                             label="vanishing gradient"))
+
+
 @pytest.mark.parametrize("K,V,Nqk", [(64, 64, 0), (64, 16, 1)])
 def test_single_step_decode_chain_bf16(K, V, Nqk):
     """Recurrent inference: T = 1 per call, the state handed from call to call (H_T -> H0),
