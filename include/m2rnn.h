@@ -88,6 +88,7 @@ int32_t m2rnn_max_chunk(const m2rnn_desc *desc);
 /* Name of the kernel variant that serves this descriptor's forward (bwd = 0) or backward
  * (bwd != 0): "tile<K,V,RB>" (matrix-core kernel, a 16-row block spread over V/16 waves, RB
  * row blocks per workgroup), "rowwave<K,V>" (matrix-core forward, one wave per 16-row block),
+ * "decode<K,V>" (T = 1: the single-launch latency kernel of recurrent inference),
  * "generic<f32>" / "generic<bf16>" (plain fp32 vector-ALU kernels), or "invalid descriptor".
  * Static storage.  For profiling and for tests that must reach every variant. */
 const char *m2rnn_route_string(const m2rnn_desc *desc, int bwd);

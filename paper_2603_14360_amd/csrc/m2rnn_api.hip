@@ -30,7 +30,7 @@ m2rnn_status check_desc(const m2rnn_desc *d) {
 
 // Which kernel family serves this descriptor.  The checkpoint layout is common
 // to all families, so forward and backward may come from different ones.
-enum Family { kGeneric = 0, kMfma = 1, kRowWave = 2 };
+enum Family { kGeneric = 0, kMfma = 1, kRowWave = 2, kDecode = 3 };
 
 Family family_of(const m2rnn_desc *d) {  // backward (it owns the chunk limits)
   if (d->io == M2RNN_BF16 && mfma_supported(d->K, d->V)) return kMfma;
@@ -38,6 +38,8 @@ Family family_of(const m2rnn_desc *d) {  // backward (it owns the chunk limits)
 }
 
 Family fwd_family_of(const m2rnn_desc *d) {
+  // one token per call: the latency kernel (one launch, state through HBM once, no staging)
+  if (d->io == M2RNN_BF16 && d->T == 1 && decode_supported(d->K, d->V)) return kDecode;
   // The register-resident kernel needs no LDS exchange but one wave carries a
   // whole 16-row block; it pays off once there are enough row blocks for at
   // least two waves per SIMD (1024 SIMDs).  Below that the tiled kernel, which
@@ -51,6 +53,7 @@ Family fwd_family_of(const m2rnn_desc *d) {
 
 hipError_t run_fwd(const m2rnn_desc *d, const FwdArgs &a, hipStream_t s) {
   switch (fwd_family_of(d)) {
+    case kDecode: return decode_fwd(a, s);
     case kRowWave: return rowwave_fwd(a, s);
     case kMfma: return mfma_fwd(a, s);
     default: return generic_fwd(a, s);
@@ -79,7 +82,7 @@ size_t ckpt_bytes(const m2rnn_desc *d, int C) {
 
 size_t family_ws(const m2rnn_desc *d, int C, int bwd) {
   const Family fam = bwd ? family_of(d) : fwd_family_of(d);
-  if (fam == kRowWave) return 0;
+  if (fam == kRowWave || fam == kDecode) return 0;
   return fam == kMfma ? mfma_workspace_bytes(d->B, d->T, d->N, d->Nqk, d->K, d->V, C, bwd)
                       : generic_workspace_bytes(d->B, d->T, d->N, d->Nqk, d->K, d->V, C, bwd);
 }
@@ -174,6 +177,13 @@ const char *m2rnn_route_string(const m2rnn_desc *desc, int bwd) {
   if (check_desc(desc) != M2RNN_OK) return "invalid descriptor";
   const Family fam = bwd ? family_of(desc) : fwd_family_of(desc);
   if (fam == kGeneric) return desc->io == M2RNN_F32 ? "generic<f32>" : "generic<bf16>";
+  if (fam == kDecode) {
+#define X(K_, V_) \
+  if (desc->K == K_ && desc->V == V_) return "decode<" #K_ "," #V_ ">";
+    M2RNN_ROWWAVE_CASES(X)
+#undef X
+    return "decode<?>";
+  }
   if (fam == kRowWave) {
 #define X(K_, V_) \
   if (desc->K == K_ && desc->V == V_) return "rowwave<" #K_ "," #V_ ">";

@@ -95,4 +95,8 @@ int mfma_pick_rb(int K, int V, int units);  // row blocks per workgroup of the t
 bool rowwave_supported(int K, int V);
 hipError_t rowwave_fwd(const FwdArgs &a, hipStream_t s);
 
+// ---- single-step decode (bf16 io, V <= 64, T == 1): one launch, no staging, no workspace ----
+bool decode_supported(int K, int V);
+hipError_t decode_fwd(const FwdArgs &a, hipStream_t s);
+
 }  // namespace m2rnn

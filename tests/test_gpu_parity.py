@@ -242,12 +242,15 @@ def test_vanishing_gradient_after_large_late_dy_bf16():
                                              label="vanishing gradient"))
 
 
-@pytest.mark.parametrize("K,V,Nqk", [(64, 64, 0), (64, 16, 1)])
+@pytest.mark.parametrize("K,V,Nqk", [(64, 64, 0), (64, 16, 1), (128, 64, 0), (16, 32, 2), (32, 16, 0)])
 def test_single_step_decode_chain_bf16(K, V, Nqk):
     """Recurrent inference: T = 1 per call, the state handed from call to call (H_T -> H0),
     for a batch of sequences; every step's y and the final state against the oracle's one
-    long run."""
+    long run.  T = 1 is served by the single-launch decode kernel."""
+    from paper_2603_14360_amd import binding as mb
     B, N, steps = 24, 4, 20
+    assert mb.m2rnn_route_string(mb.make_desc(B, 1, N, K, V, mb.M2RNN_BF16, Nqk=(Nqk or None)), 0) \
+        == "decode<%d,%d>" % (K, V)
     wl = Workload("t", B, steps, N, K, V, "bf16", 123 + V, K ** -0.5, 2.0, use_H0=True, Nqk=Nqk)
     inp = make_inputs(wl)
     ref = gu.run_oracle(inp, backward=False)
@@ -264,6 +267,25 @@ def test_single_step_decode_chain_bf16(K, V, Nqk):
     errs = {"y": gu.rel_err(y, ref["y"]), "HT": gu.rel_err(H.astype(np.float64), ref["HT"])}
     _report("decode K%d V%d" % (K, V), errs)
     assert errs["y"] <= gu.TOL["bf16"] and errs["HT"] <= gu.TOL["bf16"], errs
+
+
+def test_decode_step_options_and_training_pair_bf16():
+    """The decode kernel with the forward options (residual w_r, gate function), with a zero
+    initial state (H0 = NULL), and as the forward of a T = 1 training pair (it then writes
+    checkpoint 0 for m2rnn_bwd)."""
+    from paper_2603_14360_amd.synth_inputs import make_gate_inputs, make_residual_weight
+    wl = Workload("t", 5, 1, 6, 64, 32, "bf16", 77, 0.125, 1.0, use_H0=True, use_dHT=True, Nqk=3)
+    inp = make_inputs(wl)
+    inp["w_r"] = make_residual_weight(wl)
+    inp["f"], inp["gate"] = make_gate_inputs(wl)
+    print("case decode with options, training pair", flush=True)
+    got = gu.run_gpu(inp, "bf16")
+    ref = gu.run_oracle(inp)
+    _report("decode options", gu.compare(got, ref, gu.TOL["bf16"], label="decode options"))
+    inp2 = make_inputs(Workload("t", 3, 1, 2, 32, 64, "bf16", 78, 0.125, 1.0))
+    got = gu.run_gpu(inp2, "bf16", backward=False)
+    ref = gu.run_oracle(inp2, backward=False)
+    _report("decode H0 = NULL", gu.compare(got, ref, gu.TOL["bf16"], label="decode null H0"))
 
 
 def test_graph_capture_and_replay_bf16():
