@@ -196,6 +196,49 @@ m2rnn_status m2rnn_bwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
                            size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The scan's two neighbours in the block (layer equations of the "M2RNN Block" section), each
+ * as one pass over its tensors.  All tensors are device pointers, dense, 16-byte aligned; io
+ * is an m2rnn_dtype and types x / out / w / bias (resp. y / a / out / w / dout / dy / da);
+ * weight gradients are fp32, overwritten, and summed over (b, t) in a fixed order.
+ *
+ * Prologue of q, k, v:  out = SiLU(conv1d(x)): depthwise causal convolution of kernel size 4
+ * along t, zero padding on the left, tap j of w[c][.] meets step t - 3 + j (tap 3 is the
+ * current step), then SiLU(u) = u sigmoid(u).
+ *   x, out, dout, dx [B,T,C]   w [C,4]   bias [C] or NULL (the convolution's own bias; the
+ *   paper prints none)   dw [C,4] fp32   dbias [C] fp32 or NULL.   C: a multiple of 8.
+ *   workspace: m2rnn_conv_silu_workspace_bytes(B, T, C) bytes (backward only).
+ *
+ * Epilogue of y:  out = RMSNorm(y (.) g), g = SiLU(a), a the output gate's pre-activation:
+ *   x_i = y_i g_i,  s = 1 / sqrt(mean_i x_i^2 + eps),  out_i = w_i x_i s   over ALL D = N V
+ *   features of a token (the "RMSNormTP Module" appendix normalises over the features of all
+ *   heads; eps = 0 is the printed formula); backward as printed there:
+ *   p_i = w_i dout_i, r = sum_i p_i x_i, dx_i = s p_i - r s^3 x_i / D, dw_i = sum_{b,t} dout_i x_i s,
+ *   then dy = dx (.) g and da = dx (.) y SiLU'(a).
+ *   y, a, out, dout, dy, da [B,T,D]   w [D]   dw [D] fp32   s [B,T] fp32: the inverse norm
+ *   the appendix caches for the backward; out of _fwd (NULL: not wanted), in of _bwd (NULL:
+ *   recomputed).   D: a multiple of 8, at most 4096.   eps >= 0.
+ *   workspace: m2rnn_gated_rmsnorm_workspace_bytes(B, T, D) bytes (backward only).
+ *
+ * Errors as for the scan: M2RNN_ERR_DTYPE / _SHAPE / _NULL / _ALIGN / _WORKSPACE on the host
+ * before anything is launched, M2RNN_ERR_HIP for a failed launch.
+ */
+size_t m2rnn_conv_silu_workspace_bytes(int32_t B, int32_t T, int32_t C);
+m2rnn_status m2rnn_conv_silu_fwd(int32_t B, int32_t T, int32_t C, int32_t io, const void *x,
+                                 const void *w, const void *bias, void *out, void *hip_stream);
+m2rnn_status m2rnn_conv_silu_bwd(int32_t B, int32_t T, int32_t C, int32_t io, const void *x,
+                                 const void *w, const void *bias, const void *dout, void *dx,
+                                 float *dw, float *dbias, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream);
+size_t m2rnn_gated_rmsnorm_workspace_bytes(int32_t B, int32_t T, int32_t D);
+m2rnn_status m2rnn_gated_rmsnorm_fwd(int32_t B, int32_t T, int32_t D, int32_t io, const void *y,
+                                     const void *a, const void *w, float eps, void *out, float *s,
+                                     void *hip_stream);
+m2rnn_status m2rnn_gated_rmsnorm_bwd(int32_t B, int32_t T, int32_t D, int32_t io, const void *y,
+                                     const void *a, const void *w, float eps, const float *s,
+                                     const void *dout, void *dy, void *da, float *dw,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * m2rnn_fwd_opt for callers that cannot allocate device memory or size a workspace: code
  * under HIP graph capture, tight serving loops (single-step or short-segment decode),
  * harnesses that forbid hipMalloc.  It takes no workspace: the scratch the forward needs for

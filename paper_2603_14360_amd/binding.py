@@ -16,7 +16,10 @@ M2RNN_BF16 = 1
 
 EXPORTS = ("m2rnn_status_string", "m2rnn_default_chunk", "m2rnn_max_chunk",
            "m2rnn_ckpt_bytes", "m2rnn_workspace_bytes", "m2rnn_fwd", "m2rnn_bwd",
-           "m2rnn_fwd_opt", "m2rnn_bwd_opt", "m2rnn_fwd_static", "m2rnn_route_string")
+           "m2rnn_fwd_opt", "m2rnn_bwd_opt", "m2rnn_fwd_static", "m2rnn_route_string",
+           "m2rnn_conv_silu_workspace_bytes", "m2rnn_conv_silu_fwd", "m2rnn_conv_silu_bwd",
+           "m2rnn_gated_rmsnorm_workspace_bytes", "m2rnn_gated_rmsnorm_fwd",
+           "m2rnn_gated_rmsnorm_bwd")
 M2RNN_STATIC_SCRATCH_BYTES = 8 << 20
 
 
@@ -77,6 +80,19 @@ def lib():
         L.m2rnn_route_string.argtypes = [dp, ctypes.c_int]
         L.m2rnn_fwd_static.restype = ctypes.c_int
         L.m2rnn_fwd_static.argtypes = [dp, op] + [vp] * 9 + [vp]
+        i32, fl = ctypes.c_int32, ctypes.c_float
+        L.m2rnn_conv_silu_workspace_bytes.restype = sz
+        L.m2rnn_conv_silu_workspace_bytes.argtypes = [i32] * 3
+        L.m2rnn_conv_silu_fwd.restype = ctypes.c_int
+        L.m2rnn_conv_silu_fwd.argtypes = [i32] * 4 + [vp] * 5
+        L.m2rnn_conv_silu_bwd.restype = ctypes.c_int
+        L.m2rnn_conv_silu_bwd.argtypes = [i32] * 4 + [vp] * 8 + [sz, vp]
+        L.m2rnn_gated_rmsnorm_workspace_bytes.restype = sz
+        L.m2rnn_gated_rmsnorm_workspace_bytes.argtypes = [i32] * 3
+        L.m2rnn_gated_rmsnorm_fwd.restype = ctypes.c_int
+        L.m2rnn_gated_rmsnorm_fwd.argtypes = [i32] * 4 + [vp] * 3 + [fl] + [vp] * 3
+        L.m2rnn_gated_rmsnorm_bwd.restype = ctypes.c_int
+        L.m2rnn_gated_rmsnorm_bwd.argtypes = [i32] * 4 + [vp] * 3 + [fl] + [vp] * 6 + [sz, vp]
         _lib = L
     return _lib
 
@@ -183,6 +199,58 @@ def m2rnn_bwd_opt(desc, opts, q, k, v, f, W, H0, ckpt, dy, dHT, dq, dk, dv, df, 
     if check and rc != 0:
         raise M2RNNError(rc, "m2rnn_bwd_opt")
     return rc
+
+
+def _io_code(t):
+    import torch
+    return M2RNN_BF16 if t.dtype == torch.bfloat16 else M2RNN_F32
+
+
+def _check(rc, where, check):
+    if check and rc != 0:
+        raise M2RNNError(rc, where)
+    return rc
+
+
+def m2rnn_conv_silu_workspace_bytes(B, T, C):
+    return int(lib().m2rnn_conv_silu_workspace_bytes(B, T, C))
+
+
+def m2rnn_conv_silu_fwd(x, w, bias, out, stream=None, check=True):
+    """out = SiLU(causal depthwise conv1d(4) of x [B,T,C]); w [C,4], bias [C] or None."""
+    B, T, C = x.shape
+    rc = lib().m2rnn_conv_silu_fwd(B, T, C, _io_code(x), _ptr(x), _ptr(w), _ptr(bias), _ptr(out),
+                                   ctypes.c_void_p(stream or 0))
+    return _check(rc, "m2rnn_conv_silu_fwd", check)
+
+
+def m2rnn_conv_silu_bwd(x, w, bias, dout, dx, dw, dbias, workspace, stream=None, check=True):
+    B, T, C = x.shape
+    rc = lib().m2rnn_conv_silu_bwd(B, T, C, _io_code(x), _ptr(x), _ptr(w), _ptr(bias), _ptr(dout),
+                                   _ptr(dx), _ptr(dw), _ptr(dbias), _ptr(workspace),
+                                   _nbytes(workspace), ctypes.c_void_p(stream or 0))
+    return _check(rc, "m2rnn_conv_silu_bwd", check)
+
+
+def m2rnn_gated_rmsnorm_workspace_bytes(B, T, D):
+    return int(lib().m2rnn_gated_rmsnorm_workspace_bytes(B, T, D))
+
+
+def m2rnn_gated_rmsnorm_fwd(y, a, w, eps, out, s, stream=None, check=True):
+    """out = RMSNorm(y (.) SiLU(a)) over the last axis of [B,T,D]; s [B,T] fp32 or None."""
+    B, T, D = y.shape
+    rc = lib().m2rnn_gated_rmsnorm_fwd(B, T, D, _io_code(y), _ptr(y), _ptr(a), _ptr(w), float(eps),
+                                       _ptr(out), _ptr(s), ctypes.c_void_p(stream or 0))
+    return _check(rc, "m2rnn_gated_rmsnorm_fwd", check)
+
+
+def m2rnn_gated_rmsnorm_bwd(y, a, w, eps, s, dout, dy, da, dw, workspace, stream=None, check=True):
+    B, T, D = y.shape
+    rc = lib().m2rnn_gated_rmsnorm_bwd(B, T, D, _io_code(y), _ptr(y), _ptr(a), _ptr(w), float(eps),
+                                       _ptr(s), _ptr(dout), _ptr(dy), _ptr(da), _ptr(dw),
+                                       _ptr(workspace), _nbytes(workspace),
+                                       ctypes.c_void_p(stream or 0))
+    return _check(rc, "m2rnn_gated_rmsnorm_bwd", check)
 
 
 # --------------------------------------------------------------------------

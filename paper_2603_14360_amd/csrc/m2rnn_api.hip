@@ -317,4 +317,87 @@ m2rnn_status m2rnn_bwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
   return e == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
 }
 
+// ---- the scan's neighbours in the block ----
+
+static m2rnn_status check_block(int32_t B, int32_t T, int32_t F, int32_t io) {
+  if (io != M2RNN_F32 && io != M2RNN_BF16) return M2RNN_ERR_DTYPE;
+  if (B < 0 || T < 0 || F < 8 || F % 8 != 0) return M2RNN_ERR_SHAPE;
+  if ((double)B * (double)(T > 0 ? T : 1) * F > 1e15) return M2RNN_ERR_SHAPE;
+  return M2RNN_OK;
+}
+
+size_t m2rnn_conv_silu_workspace_bytes(int32_t B, int32_t T, int32_t C) {
+  return check_block(B, T, C, M2RNN_F32) == M2RNN_OK ? conv_silu_scratch_bytes(B, T, C) : 0;
+}
+
+m2rnn_status m2rnn_conv_silu_fwd(int32_t B, int32_t T, int32_t C, int32_t io, const void *x,
+                                 const void *w, const void *bias, void *out, void *hip_stream) {
+  m2rnn_status st = check_block(B, T, C, io);
+  if (st != M2RNN_OK) return st;
+  const bool any = (size_t)B * T > 0;
+  if (!w || (any && (!x || !out))) return M2RNN_ERR_NULL;
+  const void *ptrs[] = {x, w, bias, out};
+  for (const void *p : ptrs)
+    if (misaligned(p)) return M2RNN_ERR_ALIGN;
+  return conv_silu_fwd(B, T, C, io, x, w, bias, out, (hipStream_t)hip_stream) == hipSuccess
+             ? M2RNN_OK : M2RNN_ERR_HIP;
+}
+
+m2rnn_status m2rnn_conv_silu_bwd(int32_t B, int32_t T, int32_t C, int32_t io, const void *x,
+                                 const void *w, const void *bias, const void *dout, void *dx,
+                                 float *dw, float *dbias, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream) {
+  m2rnn_status st = check_block(B, T, C, io);
+  if (st != M2RNN_OK) return st;
+  const bool any = (size_t)B * T > 0;
+  if (!w || !dw || (any && (!x || !dout || !dx))) return M2RNN_ERR_NULL;
+  const void *ptrs[] = {x, w, bias, dout, dx, dw, dbias, workspace};
+  for (const void *p : ptrs)
+    if (misaligned(p)) return M2RNN_ERR_ALIGN;
+  if (!workspace) return M2RNN_ERR_NULL;
+  if (workspace_bytes < conv_silu_scratch_bytes(B, T, C)) return M2RNN_ERR_WORKSPACE;
+  return conv_silu_bwd(B, T, C, io, x, w, bias, dout, dx, dw, dbias, (float *)workspace,
+                       (hipStream_t)hip_stream) == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
+}
+
+size_t m2rnn_gated_rmsnorm_workspace_bytes(int32_t B, int32_t T, int32_t D) {
+  if (check_block(B, T, D, M2RNN_F32) != M2RNN_OK || D > gated_rmsnorm_max_features()) return 0;
+  return gated_rmsnorm_scratch_bytes(B, T, D);
+}
+
+m2rnn_status m2rnn_gated_rmsnorm_fwd(int32_t B, int32_t T, int32_t D, int32_t io, const void *y,
+                                     const void *a, const void *w, float eps, void *out, float *s,
+                                     void *hip_stream) {
+  m2rnn_status st = check_block(B, T, D, io);
+  if (st != M2RNN_OK) return st;
+  if (D > gated_rmsnorm_max_features() || !(eps >= 0.f)) return M2RNN_ERR_SHAPE;
+  const bool any = (size_t)B * T > 0;
+  if (!w || (any && (!y || !a || !out))) return M2RNN_ERR_NULL;
+  const void *ptrs[] = {y, a, w, out};
+  for (const void *p : ptrs)
+    if (misaligned(p)) return M2RNN_ERR_ALIGN;
+  if (((uintptr_t)s & 3u) != 0) return M2RNN_ERR_ALIGN;
+  return gated_rmsnorm_fwd(B, T, D, io, y, a, w, eps, out, s, (hipStream_t)hip_stream) == hipSuccess
+             ? M2RNN_OK : M2RNN_ERR_HIP;
+}
+
+m2rnn_status m2rnn_gated_rmsnorm_bwd(int32_t B, int32_t T, int32_t D, int32_t io, const void *y,
+                                     const void *a, const void *w, float eps, const float *s,
+                                     const void *dout, void *dy, void *da, float *dw,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+  m2rnn_status st = check_block(B, T, D, io);
+  if (st != M2RNN_OK) return st;
+  if (D > gated_rmsnorm_max_features() || !(eps >= 0.f)) return M2RNN_ERR_SHAPE;
+  const bool any = (size_t)B * T > 0;
+  if (!w || !dw || (any && (!y || !a || !dout || !dy || !da))) return M2RNN_ERR_NULL;
+  const void *ptrs[] = {y, a, w, dout, dy, da, dw, workspace};
+  for (const void *p : ptrs)
+    if (misaligned(p)) return M2RNN_ERR_ALIGN;
+  if (((uintptr_t)s & 3u) != 0) return M2RNN_ERR_ALIGN;
+  if (!workspace) return M2RNN_ERR_NULL;
+  if (workspace_bytes < gated_rmsnorm_scratch_bytes(B, T, D)) return M2RNN_ERR_WORKSPACE;
+  return gated_rmsnorm_bwd(B, T, D, io, y, a, w, eps, s, dout, dy, da, dw, (float *)workspace,
+                           (hipStream_t)hip_stream) == hipSuccess ? M2RNN_OK : M2RNN_ERR_HIP;
+}
+
 }  // extern "C"

@@ -95,6 +95,21 @@ int mfma_pick_rb(int K, int V, int units);  // row blocks per workgroup of the t
 bool rowwave_supported(int K, int V);
 hipError_t rowwave_fwd(const FwdArgs &a, hipStream_t s);
 
+// ---- the scan's neighbours in the block: conv1d(4) + SiLU prologue, gated RMSNorm epilogue ----
+size_t conv_silu_scratch_bytes(int B, int T, int C);
+hipError_t conv_silu_fwd(int B, int T, int C, int io, const void *x, const void *w, const void *bias,
+                         void *out, hipStream_t s);
+hipError_t conv_silu_bwd(int B, int T, int C, int io, const void *x, const void *w, const void *bias,
+                         const void *dout, void *dx, float *dw, float *dbias, float *part,
+                         hipStream_t s);
+size_t gated_rmsnorm_scratch_bytes(int B, int T, int D);
+int gated_rmsnorm_max_features();
+hipError_t gated_rmsnorm_fwd(int B, int T, int D, int io, const void *y, const void *a, const void *w,
+                             float eps, void *out, float *s_out, hipStream_t s);
+hipError_t gated_rmsnorm_bwd(int B, int T, int D, int io, const void *y, const void *a, const void *w,
+                             float eps, const float *s_in, const void *dout, void *dy, void *da,
+                             float *dw, float *part, hipStream_t s);
+
 // ---- single-step decode (bf16 io, V <= 64, T == 1): one launch, no staging, no workspace ----
 bool decode_supported(int K, int V);
 hipError_t decode_fwd(const FwdArgs &a, hipStream_t s);

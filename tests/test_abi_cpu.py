@@ -178,3 +178,27 @@ def test_every_kernel_instantiation_has_a_parity_case():
         bwd_seen.add(br)
     assert want <= fwd_seen and want <= bwd_seen, (want - fwd_seen, want - bwd_seen)
     assert want_rw <= fwd_seen, want_rw - fwd_seen
+
+
+def test_block_neighbours_validate_on_the_host():
+    """conv1d(4) + SiLU and gated RMSNorm entry points: sizes and refusals without a GPU."""
+    buf = FakeBuf(1 << 20, 1 << 30)
+    p = lambda x: ctypes.c_void_p(x.data_ptr()) if x is not None else None
+    L = mb.lib()
+    assert mb.m2rnn_conv_silu_workspace_bytes(2, 100, 64) > 0
+    assert mb.m2rnn_conv_silu_workspace_bytes(2, 100, 12) == 0          # C not a multiple of 8
+    assert mb.m2rnn_gated_rmsnorm_workspace_bytes(2, 100, 1344) > 0
+    assert mb.m2rnn_gated_rmsnorm_workspace_bytes(2, 100, 8192) == 0    # D above 4096
+    z = ctypes.c_void_p(0)
+    assert L.m2rnn_conv_silu_fwd(2, 10, 12, 1, p(buf), p(buf), None, p(buf), z) == 2
+    assert L.m2rnn_conv_silu_fwd(2, 10, 16, 5, p(buf), p(buf), None, p(buf), z) == 3
+    assert L.m2rnn_conv_silu_fwd(2, 10, 16, 1, None, p(buf), None, p(buf), z) == 1
+    assert L.m2rnn_conv_silu_fwd(2, 10, 16, 1, ctypes.c_void_p(buf.addr + 4), p(buf), None, p(buf), z) == 4
+    assert L.m2rnn_conv_silu_bwd(2, 10, 16, 1, p(buf), p(buf), None, p(buf), p(buf), p(buf), None,
+                                 p(buf), 16, z) == 5
+    assert L.m2rnn_gated_rmsnorm_fwd(2, 10, 8192, 1, p(buf), p(buf), p(buf), 0.0, p(buf), None, z) == 2
+    assert L.m2rnn_gated_rmsnorm_fwd(2, 10, 64, 1, p(buf), p(buf), p(buf), -1.0, p(buf), None, z) == 2
+    assert L.m2rnn_gated_rmsnorm_bwd(2, 10, 64, 1, p(buf), p(buf), p(buf), 0.0, None, p(buf), p(buf),
+                                     p(buf), p(buf), p(buf), 16, z) == 5
+    assert L.m2rnn_gated_rmsnorm_bwd(2, 10, 64, 1, p(buf), p(buf), p(buf), 0.0, None, p(buf), None,
+                                     p(buf), p(buf), p(buf), 1 << 30, z) == 1
