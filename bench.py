@@ -31,10 +31,30 @@ ALU_OPS = {"fwd": (7, 2), "bwd": (14, 2)}
 TRANS_SLOTS = 2                       # issue slots of v_exp_f32 / v_rcp_f32 relative to v_fma_f32
 PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9  # lane-ops per second, packed fp32 not used
 
-# HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs of this script
-# (FETCH_SIZE, then WRITE_SIZE; each scaled by what the same counter reads for the
-# --calib-copy-mib copy: x2.000 and x1.000).  Summary: profiles/c3_fwd_bwd_pmc_counters.txt.
-MEASURED_TRAFFIC_BYTES = {"C3": 440049 * 1024 * 2.000 + 672730 * 1024 * 1.000}
+# HBM bytes per launch of the dominant kernel (the backward scan kernel; the forward one for
+# forward-only workloads), from two rocprofv3 --pmc runs of this script (FETCH_SIZE, then
+# WRITE_SIZE, in KiB; each scaled by what the same counter reads for the --calib-copy-mib
+# copy).  These are figures of the profiled runs whose summaries are named here, not of the
+# run that prints them: (fetch KiB, fetch scale, write KiB, write scale, summary file).
+MEASURED_TRAFFIC = {
+    "C3": (440049, 2.000, 672730, 1.000, "profiles/c3_fwd_bwd_pmc_counters.txt"),
+}
+
+MFMA_PEAK = 2.5e15   # dense fp16 / bf16 flop/s
+HBM_PEAK = 8.0e12    # bytes/s
+
+
+def algorithmic_bytes(wl, chunk, kind):
+    """HBM bytes the method itself must move per call: the per-step vectors of every
+    (b, n) unit-step (q, k, v, f in, y out; for the backward also dy in and dq, dk, dv, df
+    out) plus one fp32 checkpoint per chunk and unit (written by the forward, read by the
+    backward).  W, H0, H_T, dW, dH0 are per launch and negligible."""
+    io = 2 if wl.io == "bf16" else 4
+    unit_steps = wl.B * wl.N * wl.T
+    ck = wl.B * wl.N * -(-wl.T // chunk) * wl.K * wl.V * 4 if wl.backward else 0
+    if kind == "fwd":
+        return unit_steps * ((2 * wl.K + 2 * wl.V) * io + 4) + ck
+    return unit_steps * ((2 * wl.K + 2 * wl.V) * io + (2 * wl.K + wl.V) * io + 8) + ck
 
 
 def alu_slots(kind):
@@ -74,6 +94,103 @@ def cpu_baseline(wl, inp):
                                                     "+bwd" if wl.backward else "", dt)}
 
 
+def decode_latency():
+    """One decode step (m2rnn_fwd with T = 1, state handed from call to call): microseconds per
+    call issued eagerly and per step inside a replayed HIP graph of 16 steps."""
+    import torch
+    from paper_2603_14360_amd import binding as mb
+    rows = []
+    for (B, N, Nqk, K, V) in [(1, 16, 16, 64, 64), (8, 84, 1, 64, 16), (256, 16, 16, 64, 64)]:
+        d = mb.make_desc(B, 1, N, K, V, mb.M2RNN_BF16, Nqk=Nqk)
+        q = (torch.randn(B, 1, Nqk, K, device="cuda") * 0.125).bfloat16()
+        k = (torch.randn(B, 1, Nqk, K, device="cuda") * 0.125).bfloat16()
+        v = (torch.randn(B, 1, N, V, device="cuda") * 0.125).bfloat16()
+        f = torch.rand(B, 1, N, device="cuda")
+        W = (torch.randn(N, V, V, device="cuda") / V ** 0.5).bfloat16()
+        H = [torch.randn(B, N, K, V, device="cuda") * 0.1, torch.empty(B, N, K, V, device="cuda")]
+        y = torch.empty(B, 1, N, V, device="cuda", dtype=torch.bfloat16)
+        ws = torch.empty(max(256, mb.m2rnn_workspace_bytes(d, 0)), dtype=torch.uint8, device="cuda")
+
+        def step(i, stream):
+            mb.m2rnn_fwd(d, q, k, v, f, W, H[i & 1], y, H[(i + 1) & 1], None, ws, stream=stream)
+        st = torch.cuda.current_stream().cuda_stream
+        for i in range(20):
+            step(i, st)
+        torch.cuda.synchronize()
+        n = 2000
+        t0 = time.perf_counter()
+        for i in range(n):
+            step(i, st)
+        torch.cuda.synchronize()
+        eager = (time.perf_counter() - t0) / n * 1e6
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for i in range(4):
+                step(i, side.cuda_stream)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for i in range(16):
+                step(i, torch.cuda.current_stream().cuda_stream)
+        for _ in range(5):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(200):
+            g.replay()
+        torch.cuda.synchronize()
+        graph = (time.perf_counter() - t0) / (200 * 16) * 1e6
+        rows.append({"states": B * N, "K": K, "V": V, "route": mb.m2rnn_route_string(d, 0),
+                     "eager_us_per_call": round(eager, 2), "graph_us_per_step": round(graph, 2),
+                     "state_traffic_GBps_in_graph": round(2 * B * N * K * V * 4 / (graph * 1e-6) / 1e9, 1)})
+    return rows
+
+
+def block_kernels_bandwidth():
+    """The scan's neighbours in the block at the C3 layer width (1024 channels): algorithmic
+    HBM bytes (each tensor once) over the HIP-event time of the call, against 8 TB/s."""
+    import numpy as np
+    import torch
+    from paper_2603_14360_amd import binding as mb
+    B, T, C = 8, 4096, 1024
+    bf = torch.bfloat16
+    x = torch.randn(B, T, C, device="cuda").to(bf)
+    a = torch.randn(B, T, C, device="cuda").to(bf)
+    d = torch.randn(B, T, C, device="cuda").to(bf)
+    w4 = (torch.randn(C, 4, device="cuda") * 0.5).to(bf)
+    bias = torch.randn(C, device="cuda").to(bf)
+    wn = torch.rand(C, device="cuda").to(bf)
+    o1, o2 = torch.empty_like(x), torch.empty_like(x)
+    dw4, db = torch.empty(C, 4, device="cuda"), torch.empty(C, device="cuda")
+    dwn, sc = torch.empty(C, device="cuda"), torch.empty(B, T, device="cuda")
+    ws = torch.empty(max(mb.m2rnn_conv_silu_workspace_bytes(B, T, C),
+                         mb.m2rnn_gated_rmsnorm_workspace_bytes(B, T, C), 256), dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    n = B * T * C * 2   # bytes of one bf16 activation tensor
+    calls = {
+        "conv_silu_fwd": (lambda: mb.m2rnn_conv_silu_fwd(x, w4, bias, o1, stream=st), 2 * n),
+        "conv_silu_bwd": (lambda: mb.m2rnn_conv_silu_bwd(x, w4, bias, d, o1, dw4, db, ws, stream=st), 3 * n),
+        "gated_rmsnorm_fwd": (lambda: mb.m2rnn_gated_rmsnorm_fwd(x, a, wn, 1e-5, o1, sc, stream=st), 3 * n),
+        "gated_rmsnorm_bwd": (lambda: mb.m2rnn_gated_rmsnorm_bwd(x, a, wn, 1e-5, sc, d, o1, o2, dwn, ws, stream=st), 5 * n),
+    }
+    out = {}
+    for name, (fn, nbytes) in calls.items():
+        for _ in range(3):
+            fn()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        for e0, e1 in ev:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in ev]))
+        out[name] = {"ms": round(ms, 4), "algorithmic_GB": round(nbytes / 1e9, 3),
+                     "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "hbm_frac": round(nbytes / (ms * 1e-3) / HBM_PEAK, 3)}
+    return {"shape": "B=%d T=%d C=D=%d bf16" % (B, T, C), "kernels": out}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +198,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true",
+                    help="instead of the headline line, print one JSON line with the decode-step "
+                         "latency and the bandwidth of the block's neighbour kernels")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run a plain elementwise copy of this many MiB (read) + as many "
                          "(write) three times before the warm-up: the yardstick that scales "
@@ -96,6 +216,10 @@ def main():
     from paper_2603_14360_amd.synth_inputs import WORKLOADS, make_inputs
 
     mb.lib()  # fail loudly when the HIP library is missing
+    if args.extras:
+        print(json.dumps({"decode_step_latency": decode_latency(),
+                          "block_neighbours": block_kernels_bandwidth()}))
+        return
     wl = WORKLOADS[args.workload]
     inp = make_inputs(wl)
     io_dt = torch.bfloat16 if wl.io == "bf16" else torch.float32
@@ -149,6 +273,14 @@ def main():
     dom_ms = bwd_ms if wl.backward else fwd_ms
     achieved = elem_steps * alu_slots(dom) / (dom_ms * 1e-3)
     step_slots = alu_slots("fwd") + (alu_slots("bwd") if wl.backward else 0)
+    chunk = mb.m2rnn_default_chunk(scan.desc)
+    mfma_flops = elem_steps * wl.V * (2 + (6 if wl.backward else 0))
+    alg_bytes = algorithmic_bytes(wl, chunk, "fwd") + (algorithmic_bytes(wl, chunk, "bwd") if wl.backward else 0)
+    traffic = traffic_source = None
+    if wl.name in MEASURED_TRAFFIC:
+        fk, fs, wk, ws_, src = MEASURED_TRAFFIC[wl.name]
+        traffic = (fk * fs + wk * ws_) * 1024.0
+        traffic_source = src + " (a profiled run of this command, not this run)"
     out = {
         "metric": "M2RNN fwd+bwd tokens/s on 1 MI355X" if wl.backward else "M2RNN fwd tokens/s on 1 MI355X",
         "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s",
@@ -159,16 +291,25 @@ def main():
         "config": {"workload": "%s: B=%d N=%d%s K=%d V=%d T=%d %s io, fwd%s" % (
             wl.name, wl.B, wl.N, " (Nqk=%d)" % wl.Nqk if wl.Nqk else "", wl.K, wl.V, wl.T, wl.io,
             "+bwd" if wl.backward else ""),
-            "tokens_per_step": tokens, "chunk": mb.m2rnn_default_chunk(scan.desc)},
+            "tokens_per_step": tokens, "chunk": chunk,
+            "routes": [mb.m2rnn_route_string(scan.desc, 0)] + ([mb.m2rnn_route_string(scan.desc, 1)] if wl.backward else [])},
         "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
         "roofline": {
-            "bound": "alu", "kernel": "m2rnn_%s (scan kernel of the %s call)" % (dom, dom),
+            "bound": "alu",
+            "kernel": "m2rnn_%s call: the %s scan kernel and its ordered-sum epilogues (the scan "
+                      "kernel alone is ~98 %% of it: profiles/)" % (dom, "backward" if wl.backward else "forward"),
             "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
             "frac": achieved / PEAK_LANE_OPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+            "traffic": traffic,
+            "traffic_source": traffic_source,
             "step_frac": elem_steps * step_slots / (ms_per_step * 1e-3) / PEAK_LANE_OPS,
             "fwd_frac": elem_steps * alu_slots("fwd") / (fwd_ms * 1e-3) / PEAK_LANE_OPS,
-            "mfma_tflops": elem_steps * wl.V * (2 + (6 if wl.backward else 0)) / (ms_per_step * 1e-3) / 1e12,
+            # the other two rooflines of the metric, for the whole step (small by construction:
+            # the path is bound by tanh and gating on the vector ALUs)
+            "mfma_tflops": mfma_flops / (ms_per_step * 1e-3) / 1e12,
+            "mfma_frac": mfma_flops / (ms_per_step * 1e-3) / MFMA_PEAK,
+            "hbm_algorithmic_GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
+            "hbm_frac": alg_bytes / (ms_per_step * 1e-3) / HBM_PEAK,
         },
     }
     if not args.no_cpu_baseline:

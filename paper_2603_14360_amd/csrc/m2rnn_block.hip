@@ -213,12 +213,26 @@ __global__ void __launch_bounds__(256)
   }
 }
 
-__global__ void conv_sum_kernel(const float *__restrict__ part, float *__restrict__ dw,
-                                float *__restrict__ dbias, int C, int R) {
+// Ordered sum of R partial rows of E floats, in two levels so that it is both parallel and
+// reproducible: group g (blockIdx.y) adds its rows g*per .. (g+1)*per - 1 in increasing order
+// into row g of `lvl` (kSumGroups rows behind the partials); the second level adds those.
+constexpr int kSumGroups = 32;
+__global__ void ordered_sum_level1_kernel(const float *__restrict__ part, float *__restrict__ lvl,
+                                          int E, int R) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  const int per = (R + kSumGroups - 1) / kSumGroups;
+  const int r0 = blockIdx.y * per, r1 = r0 + per < R ? r0 + per : R;
+  float s = 0.f;
+  for (int r = r0; r < r1; ++r) s += part[(size_t)r * E + e];
+  lvl[(size_t)blockIdx.y * E + e] = s;
+}
+__global__ void conv_sum_kernel(const float *__restrict__ lvl, float *__restrict__ dw,
+                                float *__restrict__ dbias, int C, int groups) {
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= C * (kTaps + 1)) return;
   float s = 0.f;
-  for (int r = 0; r < R; ++r) s += part[(size_t)r * C * (kTaps + 1) + e];
+  for (int r = 0; r < groups; ++r) s += lvl[(size_t)r * C * (kTaps + 1) + e];
   const int c = e / (kTaps + 1), j = e - c * (kTaps + 1);
   if (j < kTaps) dw[c * kTaps + j] = s;
   else if (dbias) dbias[c] = s;
@@ -340,16 +354,19 @@ __global__ void __launch_bounds__(256)
   }
 }
 
-__global__ void norm_sum_kernel(const float *__restrict__ part, float *__restrict__ dw, int D, int R) {
+__global__ void norm_sum_kernel(const float *__restrict__ lvl, float *__restrict__ dw, int D, int groups) {
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= D) return;
   float s = 0.f;
-  for (int r = 0; r < R; ++r) s += part[(size_t)r * D + e];
+  for (int r = 0; r < groups; ++r) s += lvl[(size_t)r * D + e];
   dw[e] = s;
 }
 
-constexpr int kConvRows = 512;   // partial rows of the convolution's dw / dbias sums
-constexpr int kNormWaves = 1024; // partial rows of the norm's dw sum
+// Partial rows of the weight-gradient sums.  Many rows = many independent walkers (these
+// kernels are bound by memory latency per walker, not by arithmetic); the partials cost
+// 2 x rows x features x 4 B of extra traffic, about a fifth of the tensors' own at these caps.
+constexpr int kConvRows = 2048;  // of the convolution's dw / dbias sums
+constexpr int kNormWaves = 4096; // of the norm's dw sum
 
 inline int conv_rows(int B, int T) {
   const long long rows = (long long)B * ((T + kSeg - 1) / kSeg);
@@ -364,10 +381,10 @@ inline int norm_waves(size_t tokens) {
 }  // namespace
 
 size_t conv_silu_scratch_bytes(int B, int T, int C) {
-  return align256((size_t)conv_rows(B, T) * C * (kTaps + 1) * sizeof(float));
+  return align256((size_t)(conv_rows(B, T) + kSumGroups) * C * (kTaps + 1) * sizeof(float));
 }
 size_t gated_rmsnorm_scratch_bytes(int B, int T, int D) {
-  return align256((size_t)norm_waves((size_t)B * T) * D * sizeof(float));
+  return align256((size_t)(norm_waves((size_t)B * T) + kSumGroups) * D * sizeof(float));
 }
 int gated_rmsnorm_max_features() { return kMaxVecPerLane * 64 * 8; }
 
@@ -400,8 +417,13 @@ static hipError_t conv_bwd_t(int B, int T, int C, const void *x, const void *w, 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(conv_sum_kernel, dim3((C * (kTaps + 1) + 255) / 256), dim3(256), 0, s,
-                     (const float *)part, dw, dbias, C, any ? R : 0);
+  const int E = C * (kTaps + 1);
+  float *lvl = part + (size_t)R * E;
+  if (any)
+    hipLaunchKernelGGL(ordered_sum_level1_kernel, dim3((E + 255) / 256, kSumGroups), dim3(256), 0, s,
+                       (const float *)part, lvl, E, R);
+  hipLaunchKernelGGL(conv_sum_kernel, dim3((E + 255) / 256), dim3(256), 0, s, (const float *)lvl, dw,
+                     dbias, C, any ? kSumGroups : 0);
   return hipGetLastError();
 }
 hipError_t conv_silu_bwd(int B, int T, int C, int io, const void *x, const void *w, const void *bias,
@@ -440,8 +462,12 @@ static hipError_t norm_bwd_t(int B, int T, int D, const void *y, const void *a, 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(norm_sum_kernel, dim3((D + 255) / 256), dim3(256), 0, s, (const float *)part, dw, D,
-                     tokens > 0 ? R : 0);
+  float *lvl = part + (size_t)R * D;
+  if (tokens > 0)
+    hipLaunchKernelGGL(ordered_sum_level1_kernel, dim3((D + 255) / 256, kSumGroups), dim3(256), 0, s,
+                       (const float *)part, lvl, D, R);
+  hipLaunchKernelGGL(norm_sum_kernel, dim3((D + 255) / 256), dim3(256), 0, s, (const float *)lvl, dw, D,
+                     tokens > 0 ? kSumGroups : 0);
   return hipGetLastError();
 }
 hipError_t gated_rmsnorm_bwd(int B, int T, int D, int io, const void *y, const void *a, const void *w,

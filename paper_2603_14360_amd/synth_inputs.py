@@ -50,6 +50,9 @@ WORKLOADS = {
     # the paper's own layer shape (state-size appendix: K = 64, V = 16; 84 heads at the 410M
     # scale; q and k shared by all heads, i.e. the multi-value form of Algorithms 1 and 2)
     "P1": Workload("P1", 8, 4096, 84, 64, 16, "bf16", 5, 0.125, 2.0, Nqk=1),
+    # a training shape with many states (B N = 512): the forward is then served by the
+    # one-wave-per-row-block kernel, the backward by the tiled one
+    "R1": Workload("R1", 32, 1024, 16, 64, 64, "bf16", 6, 0.125, 2.0),
 }
 
 
