@@ -100,11 +100,14 @@ const char *m2rnn_route_string(const m2rnn_desc *desc, int bwd);
  * descriptor or T == 0. */
 size_t m2rnn_ckpt_bytes(const m2rnn_desc *desc);
 
-/* Bytes of scratch the forward (bwd = 0) or backward (bwd != 0) call needs for
- * partial sums across workgroups.  The backward figure includes room for
- * checkpoints, used only when bwd is called with ckpt == NULL, and for the
- * two-stage sums of the option gradients (dw_r, dgate_alpha, dgate_beta); the same
- * size serves the plain and the _opt calls.  May be 0 for the forward. */
+/* Bytes of scratch a call needs for partial sums across workgroups:
+ *   bwd = 0   the forward (may be 0);
+ *   bwd = 1   the backward called WITH the forward's checkpoints (ckpt != NULL), the normal
+ *             forward-then-backward use;
+ *   bwd >= 2  the backward called with ckpt == NULL: bwd = 1 plus room for the checkpoints it
+ *             then recomputes itself (m2rnn_ckpt_bytes more).
+ * The backward figures include the two-stage sums of the option gradients (dw_r,
+ * dgate_alpha, dgate_beta); the same size serves the plain and the _opt calls. */
 size_t m2rnn_workspace_bytes(const m2rnn_desc *desc, int bwd);
 
 /*
@@ -137,7 +140,7 @@ m2rnn_status m2rnn_fwd(const m2rnn_desc *desc, const void *q, const void *k,
  *   dv     [B,T,N,V] io, out   df [B,T,N] fp32, out (gradient w.r.t. the gate value)
  *   dW     [N,V,V] fp32, out (summed over the batch)
  *   dH0    [B,N,K,V] fp32, out; NULL if not wanted
- *   workspace / workspace_bytes  at least m2rnn_workspace_bytes(desc,1)
+ *   workspace / workspace_bytes  at least m2rnn_workspace_bytes(desc, ckpt ? 1 : 2)
  */
 m2rnn_status m2rnn_bwd(const m2rnn_desc *desc, const void *q, const void *k,
                        const void *v, const float *f, const void *W,

@@ -273,7 +273,8 @@ class Scan:
         self.backward = backward
         ws = m2rnn_workspace_bytes(d, 0)
         if backward:
-            ws = max(ws, m2rnn_workspace_bytes(d, 1))
+            # (2: also room for the backward's own checkpoint pass, used by bwd(use_ckpt=False))
+            ws = max(ws, m2rnn_workspace_bytes(d, 2))
             self.ckpt = torch.empty(max(1, m2rnn_ckpt_bytes(d) // 4), dtype=torch.float32, device=dev)
             self.dq = torch.empty((B, T, d.Nqk, K), dtype=self.io_dtype, device=dev)
             self.dk = torch.empty((B, T, d.Nqk, K), dtype=self.io_dtype, device=dev)

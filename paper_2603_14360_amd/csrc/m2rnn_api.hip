@@ -89,6 +89,22 @@ size_t family_ws(const m2rnn_desc *d, int C, int bwd) {
 
 bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
 
+// Carve-up of the backward's workspace: [partial sums | own checkpoints (only when the
+// backward recomputes them itself) | dw_r scratch | gate scratch].
+struct BwdWsLayout {
+  size_t main, ckpt, dwr, gate, total;
+};
+BwdWsLayout bwd_ws(const m2rnn_desc *d, int C, bool own_ckpt) {
+  BwdWsLayout w;
+  const size_t b = family_ws(d, C, 1), f = own_ckpt ? family_ws(d, C, 0) : 0;  // pass 1 borrows `main`
+  w.main = align256(b > f ? b : f);
+  w.ckpt = own_ckpt ? align256(ckpt_bytes(d, C)) : 0;
+  w.dwr = residual_dw_r_scratch_bytes(d->N, d->V);
+  w.gate = gate_scratch_bytes(d->N);
+  w.total = w.main + w.ckpt + w.dwr + w.gate;
+  return w;
+}
+
 // Library-owned scratch of m2rnn_fwd_static: one array per GPU, alive until the process ends.
 // The name below is a host-side handle only; the device address is looked up once per device
 // (each GPU holds its own copy at its own address) and only that address is handed to kernels.
@@ -203,14 +219,7 @@ size_t m2rnn_workspace_bytes(const m2rnn_desc *desc, int bwd) {
   if (check_desc(desc) != M2RNN_OK) return 0;
   const int C = resolve_chunk(desc);
   if (!C) return 0;
-  size_t need = family_ws(desc, C, bwd ? 1 : 0);
-  if (bwd) {
-    // room for the backward's own checkpoint pass (used when ckpt == NULL)
-    const size_t fwd_need = family_ws(desc, C, 0);
-    need = align256(need > fwd_need ? need : fwd_need) + align256(ckpt_bytes(desc, C)) +
-           residual_dw_r_scratch_bytes(desc->N, desc->V) + gate_scratch_bytes(desc->N);
-  }
-  return need;
+  return bwd ? bwd_ws(desc, C, bwd >= 2).total : family_ws(desc, C, 0);
 }
 
 m2rnn_status m2rnn_fwd(const m2rnn_desc *desc, const void *q, const void *k, const void *v,
@@ -278,16 +287,17 @@ m2rnn_status m2rnn_bwd_opt(const m2rnn_desc *desc, const m2rnn_opts *opts, const
                         dv, df, dW, dH0, workspace, w_r, dw_r, ga,  gb,  dga, dgb};
   for (const void *p : ptrs)
     if (misaligned(p)) return M2RNN_ERR_ALIGN;
-  const size_t need = m2rnn_workspace_bytes(desc, 1);
+  const BwdWsLayout wl = bwd_ws(desc, C, /*own_ckpt=*/ckpt == nullptr);
+  const size_t need = wl.total;
   if (need > 0 && (!workspace || workspace_bytes < need))
     return workspace ? M2RNN_ERR_WORKSPACE : M2RNN_ERR_NULL;
 
   hipStream_t s = (hipStream_t)hip_stream;
   const Family fam = family_of(desc);
   char *ws = (char *)workspace;
-  const size_t dwr_bytes = residual_dw_r_scratch_bytes(desc->N, desc->V);
-  const size_t gate_bytes = gate_scratch_bytes(desc->N);
-  const size_t main_bytes = need - align256(ckpt_bytes(desc, C)) - dwr_bytes - gate_bytes;
+  const size_t dwr_bytes = wl.dwr;
+  const size_t gate_bytes = wl.gate;
+  const size_t main_bytes = wl.main;
   if (!ckpt && steps) {
     // The paper's pass 1, keeping one state per chunk: rerun the recurrence
     // from H0 without the readout, into the tail of the workspace.

@@ -42,8 +42,11 @@ def test_sizes():
     C = mb.m2rnn_default_chunk(d)
     assert 1 <= C <= mb.m2rnn_max_chunk(d)
     assert mb.m2rnn_ckpt_bytes(d) == 2 * 4 * ((32 + C - 1) // C) * 32 * 32 * 4
-    assert mb.m2rnn_workspace_bytes(d, 1) >= mb.m2rnn_workspace_bytes(d, 0)
-    assert mb.m2rnn_workspace_bytes(d, 1) >= mb.m2rnn_ckpt_bytes(d)
+    assert mb.m2rnn_workspace_bytes(d, 2) >= mb.m2rnn_workspace_bytes(d, 0)
+    # with the forward's checkpoints the backward needs no room for its own
+    assert mb.m2rnn_workspace_bytes(d, 2) >= mb.m2rnn_workspace_bytes(d, 1) + mb.m2rnn_ckpt_bytes(d)
+    big = mb.make_desc(8, 4096, 16, 64, 64, mb.M2RNN_BF16)
+    assert mb.m2rnn_workspace_bytes(big, 1) < mb.m2rnn_workspace_bytes(big, 2) - mb.m2rnn_ckpt_bytes(big) + 1024
     assert mb.m2rnn_ckpt_bytes(desc(T=0)) == 0
     d7 = desc(chunk=7)
     assert mb.m2rnn_ckpt_bytes(d7) == 2 * 4 * 5 * 32 * 32 * 4
