@@ -7,9 +7,9 @@
  *
  *     Z_t = tanh(H_{t-1} W_n + k_t v_t^T)        H in R^{K x V}, W_n in R^{V x V}
  *     H_t = f_t H_{t-1} + (1 - f_t) Z_t          f_t in [0,1], one scalar per (b,t,n)
- *     y_t = H_t^T q_t                            (the w_r (.) v_t residual of the
- *                                                 y equation is left to the caller,
- *                                                 as in Algorithm 1)
+ *     y_t = H_t^T q_t                            (as in Algorithm 1; the w_r (.) v_t
+ *                                                 residual of the y equation is an
+ *                                                 option: m2rnn_opts.w_r)
  *
  * and its exact back-propagation through time.  Every step runs in hand-written
  * HIP kernels; there is no CPU path.
