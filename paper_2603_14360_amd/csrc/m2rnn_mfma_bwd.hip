@@ -56,18 +56,40 @@ __device__ __forceinline__ uint2 pack4_bf16(f4_t x) {
 // iteration earlier, in reverse order.  The slot B reads in a step is the one A fills in
 // the next step, so one spare slot is enough and the checkpoint interval C can be almost
 // twice what two separate buffers would allow (chunk boundaries cost several step times).
+// Fragment read through the transposing LDS load of gfx950 (ds_read_b64_tr_b16).  Within each
+// group of 16 lanes the 16 x 8 bytes that the lanes address are taken as 64 consecutive
+// fp16 values and lane d receives values d, 16 + d, 32 + d, 48 + d of them.  With the tile
+// stored as 8-byte items (column j, rows 4 i .. 4 i + 3) -- which is what a lane of the
+// accumulator layout holds -- at byte offset 32 j + 8 i, lane d addressing item
+// (column c0 + d / 4, rows 4 (d % 4) ..) receives row d, columns c0 .. c0 + 3: the A operand of
+// the 16-row MFMAs, with no scattered 2-byte writes and no padded rows.
+__device__ __forceinline__ h4_t lds_ld_tr(const lchar *p, int off) {
+  typedef short s4_t __attribute__((ext_vector_type(4)));
+  const s4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4_t *)(p + off));
+  return __builtin_bit_cast(h4_t, v);
+}
+template <bool X32>
+__device__ __forceinline__ typename Frag<X32>::type lds_ld_frag_tr(const lchar *p, int off) {
+  if constexpr (X32) {
+    const h4_t lo = lds_ld_tr(p, off), hi = lds_ld_tr(p, off + 128);
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  } else {
+    return lds_ld_tr(p, off);
+  }
+}
+
 template <typename TL>
 struct OvLds {
-  static constexpr int ROWS = TL::ROWS, V = TL::V, LDH = TL::LDH, RB = TL::RB, CT = TL::CT,
+  static constexpr int ROWS = TL::ROWS, V = TL::V, RB = TL::RB, CT = TL::CT,
                        WAVES = TL::WAVES, KS = TL::KS;
-  static constexpr int XCH = 2 * ROWS * LDH * 2;          // a double-buffered fp16 exchange tile set
+  static constexpr int DXCH = 2 * ROWS * V * 2;           // a double-buffered fp16 exchange tile set (8-byte items, unpadded)
   // the exchange buffers also carry the end-of-chunk partials (1 KB per contributing wave):
   // dq slices of team A and dk slices of team B in A's buffer, dv of team B in B's buffer
-  static constexpr int HX_BYTES = XCH > 2 * RB * KS * 1024 ? XCH : 2 * RB * KS * 1024;
-  static constexpr int DX_BYTES = XCH > WAVES * 1024 ? XCH : WAVES * 1024;
+  static constexpr int HX_BYTES = DXCH > 2 * RB * KS * 1024 ? DXCH : 2 * RB * KS * 1024;
+  static constexpr int DX_BYTES = DXCH > WAVES * 1024 ? DXCH : WAVES * 1024;
   static constexpr int STASH_STEP = RB * CT * 64 * 8;     // one h4 per lane per tile
   static constexpr int SLOT = 2 * STASH_STEP;             // a step slot: H' tiles, then Z' tiles
-  static constexpr int VEC_A = ROWS * 4 + V * 4 + V * 4 + 16;          // c*k, v, dy (f16, padded), f
+  static constexpr int VEC_A = ROWS * 4 + V * 2 + V * 2 + 16;          // c*k, v (f16), dy (f16), f
   static constexpr int VEC_B = ROWS * 4 + V * 4 + ROWS * 2 + V * 2 + 16;  // q, dy, k f16, v f16, f
   static constexpr int PER_STEP = SLOT + VEC_A + VEC_B;
   static constexpr int FIXED = HX_BYTES + DX_BYTES + SLOT + 448;
@@ -84,9 +106,9 @@ struct OvLds {
   // the small per-step vectors sit below the stash: their offsets then fit the 16-bit
   // immediate of the LDS instructions (one base register instead of one per step)
   static constexpr int KS_ = DX + DX_BYTES;                // team A: float c*k [C][ROWS]
-  static constexpr int VS_ = KS_ + C_ * ROWS * 4;          //         float v   [C][V]
-  static constexpr int DYH_ = VS_ + C_ * V * 4;            //         half dy (scaled per step) [C][V]
-  static constexpr int FA_ = DYH_ + C_ * V * 4;            //         float f, c(1-f), 1/dy-scale of the two half rows
+  static constexpr int VS_ = KS_ + C_ * ROWS * 4;          //         half v    [C][V]
+  static constexpr int DYH_ = VS_ + C_ * V * 2;            //         half dy (scaled per step) [C][V]
+  static constexpr int FA_ = DYH_ + C_ * V * 2;            //         float f, c(1-f), 1/dy-scale of the two half rows
   static constexpr int QS_ = FA_ + C_ * 16;                // team B: float q   [C][ROWS]
   static constexpr int DYS_ = QS_ + C_ * ROWS * 4;         //         float dy  [C][V]
   static constexpr int KH_ = DYS_ + C_ * V * 4;            //         half k    [C][ROWS]
@@ -105,7 +127,7 @@ struct OvLds {
 template <typename TL, bool CLIP>
 __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdArgs a, BwdWs ws) {
   constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS, KS = TL::KS,
-                LDH = TL::LDH, WAVES = TL::WAVES;
+                WAVES = TL::WAVES;
   constexpr int THREADS = TL::THREADS;  // per team
   constexpr bool X32 = TL::X32;
   constexpr int FE = X32 ? 8 : 4;
@@ -137,13 +159,10 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   const int row_base = part * ROWS;
 
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  typedef _Float16 XRow[LDH];
-  XRow *Hx = (XRow *)(lds + L::HX);
-  XRow *Dx = (XRow *)(lds + L::DX);
   // slot of chunk step s for a chunk pushed in an iteration of parity p (see OvLds)
   auto slot_of = [&](int s, int p) { return p ? (L::NSLOT - 1 - s) : s; };
   float *kS = (float *)(lds + L::KS_);
-  float *vS = (float *)(lds + L::VS_);
+  _Float16 *vS = (_Float16 *)(lds + L::VS_);
   _Float16 *dyH = (_Float16 *)(lds + L::DYH_);
   float *fA = (float *)(lds + L::FA_);
   float *qS = (float *)(lds + L::QS_);
@@ -239,9 +258,14 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         *(f4_t *)&kS[8 * ek + 4] = f4_t{x[4], x[5], x[6], x[7]} * kC;
       }
       if (ev < VI) {
+        // (fp16 like every other copy of v that feeds the matrix core: exact for bf16
+        //  data of magnitude 6e-5 .. 6e4, and the k v^T product takes it as a
+        //  mixed-precision FMA operand)
         bf16x8_to_f32(rv, x);
-        *(f4_t *)&vS[8 * ev] = f4_t{x[0], x[1], x[2], x[3]};
-        *(f4_t *)&vS[8 * ev + 4] = f4_t{x[4], x[5], x[6], x[7]};
+        h8_t hv;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) hv[i] = (_Float16)x[i];
+        *(h8_t *)&vS[8 * ev] = hv;
       }
       if (wave_has_dy) {
         // dy_s enters the dq contraction as fp16: each step's row is scaled by a power of two
@@ -283,6 +307,10 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         return mfma_k16(af_ct, bf, acc);
     };
 
+    // state exchange of this team: written as 8-byte items (column, rows 4 ig ..), read back
+    // as row fragments through the transposing LDS load (see lds_ld_tr)
+    lchar *const aHw = (lchar *)lds + (rb * V + col0 + jl) * 32 + ig * 8;
+    const lchar *const aHr = (lchar *)lds + rb * V * 32 + 32 * FE * ig + 8 * jl;
     if (nck > 0) stage_load(nck - 1);
     for (int it = 0; it <= nck; ++it) {
       const bool active = it < nck;
@@ -301,8 +329,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
           h[r] = kC * hck[r];
           hp[r] = (_Float16)h[r];
         }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) Hx[cur * ROWS + rowb + 4 * ig + r][col0 + jl] = hp[r];
+        lds_st<h4_t>(aHw, L::HX + cur * ROWS * V * 2, hp);
       }
       lds_barrier();  // P
       // Next chunk's vectors and checkpoint travel during this chunk; issued behind the
@@ -317,10 +344,10 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         FragT af[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          af[ks] = *(const FragT *)&Hx[rd * ROWS + rowb + jl][FE * ig + 32 * ks];
+          af[ks] = lds_ld_frag_tr<X32>(aHr, L::HX + rd * ROWS * V * 2 + 1024 * ks);
         const float f = fA[s * 4 + 0], gp = fA[s * 4 + 1], m2g = -2.f * gp;
         const f4_t k4 = *(const f4_t *)&kS[s * ROWS + rowb + 4 * ig];
-        const float vj = vS[s * V + col0 + jl];
+        const float vj = (float)vS[s * V + col0 + jl];
         f4_t acc = zero4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -345,8 +372,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
           hp[r] = (_Float16)h[r];
         }
         slot[L::STASH_STEP / 8] = zp;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) Hx[wr * ROWS + rowb + 4 * ig + r][col0 + jl] = hp[r];
+        lds_st<h4_t>(aHw, L::HX + wr * ROWS * V * 2, hp);
         if (s > 0 && ct < KS) {  // dq slice of the previous step; af still holds the state after it
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks)
@@ -368,7 +394,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       }
       cur = len & 1;
       if (active && ct < KS) {  // dq of the chunk's last step, from the state after it
-        const FragT afl = *(const FragT *)&Hx[cur * ROWS + rowb + jl][FE * ig + 32 * ct];
+        const FragT afl = lds_ld_frag_tr<X32>(aHr + 1024 * ct, L::HX + cur * ROWS * V * 2);
         dqacc = dq_slice(dqacc, afl, len - 1);
       }
       lds_barrier();  // E1: exchange buffer free, it carries the dq partials now
@@ -583,8 +609,8 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     lchar *bR4 = l0 + (rowb + 4 * ig) * 4;                    // q rows (fp32)
     lchar *bR2 = l0 + (rowb + 4 * ig) * 2;                    // k rows (fp16)
     lchar *bC4 = l0 + (col0 + jl) * 4;                        // dy column (fp32)
-    lchar *bDw = l0 + ((rowb + 4 * ig) * LDH + col0 + jl) * 2;  // dS write
-    lchar *bDr = l0 + ((rowb + jl) * LDH + FE * ig) * 2;      // dS fragment read
+    lchar *bDw = l0 + (rb * V + col0 + jl) * 32 + ig * 8;     // dS write: item (column, rows 4 ig ..)
+    lchar *bDr = l0 + rb * V * 32 + 32 * FE * ig + 8 * jl;    // dS fragment read (transposing)
     lchar *bV = l0 + (FE * ig + 32 * ct) * 2;                 // v slice of the dk MFMA
     lchar *bZero = l0;                                        // wave-uniform reads (f)
     int jlB = jl;  // opaque as well: the per-step column masks (jl == s) are then built per
@@ -602,7 +628,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       FragT af[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        af[ks] = lds_ld<FragT>(bDr, L::DX + rd * ROWS * LDH * 2 + 32 * ks * 2);
+        af[ks] = lds_ld_frag_tr<X32>(bDr, L::DX + rd * ROWS * V * 2 + 1024 * ks);
       f4_t d = zero4;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -697,9 +723,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
             : "+v"(dsu.y) : "v"(G[3]), "v"(ugu.y), "v"(g3));
       }
       const h4_t dsp = __builtin_bit_cast(h4_t, dsu);
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        lds_st<_Float16>(bDw, L::DX + (wr * ROWS + r) * LDH * 2, dsp[r]);
+      lds_st<h4_t>(bDw, L::DX + wr * ROWS * V * 2, dsp);
 #pragma unroll
       for (int c2 = 0; c2 < CT; ++c2) {
         if constexpr (!EARLY_H) hfr[c2] = lds_ld<h4_t>(bH + so, c2 * 512);
