@@ -35,7 +35,7 @@ constexpr int kChunkCap = 16;  // = MFMA N: one accumulator column per step of a
 
 struct BwdWs {
   float *dvp;   // [P][B,T,N,V]      (P > 1)
-  float *dfp;   // [P*WAVES][B,T,N]  per-wave partials of df, summed by the epilogue
+  float *dfp;   // [P*WAVES][B,N,T]  per-wave partials of df, summed (and laid out as [B,T,N]) by the epilogue
   float *dWp;   // [B*N][P*RB][V][V]
   float *dqh;   // [B,T,N,K]         (Nqk != N)
   float *dkh;
@@ -185,6 +185,10 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   if (threadIdx.x < 32) ((uint32_t *)(lds + L::ZERO_))[threadIdx.x] = 0u;  // zero pad and the
                                                                           // maxima slots behind it; visible after barrier P
 
+  // gate parameters of this head, read once (a load inside the chunk loop would wait for
+  // the end-of-chunk stores issued before it)
+  const float g_alpha = a.gate_alpha ? a.gate_alpha[n] : 0.f, g_beta = a.gate_alpha ? a.gate_beta[n] : 0.f;
+
   if (teamA) {
     // =====================================================================
     // team A: recompute chunk nck-1-it into stash[it & 1], it = 0 .. nck-1
@@ -207,8 +211,6 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     const bf16_raw *const dybase = dyg + ((size_t)b * T * N + n) * V;
     const float *const fbase = fg + (size_t)b * T * N + n;
     const uint32_t kstride = (uint32_t)a.Nqk * K, vstride = (uint32_t)N * V;
-    const int ek = (tid - SH_K) & (THREADS - 1), ev = (tid - SH_V) & (THREADS - 1),
-              edy = (tid - SH_DY) & (THREADS - 1), ef = (tid - SH_F) & (THREADS - 1);
     const bool wave_has_dy = ((wave * 64 - SH_DY) & (THREADS - 1)) < VI;  // wave-uniform
     const u4_t zero_u4 = {0u, 0u, 0u, 0u};
     // The loads address memory as uniform base + 32-bit byte offset, and the per-thread part
@@ -251,6 +253,13 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     auto stage_store = [&]() {
       asm volatile("" : "+v"(rk), "+v"(rv), "+v"(rdy));
       asm volatile("" : "+v"(rf), "+v"(hck[0]), "+v"(hck[1]), "+v"(hck[2]), "+v"(hck[3]));
+      // (item indices rebuilt from the thread index on the spot: kept in registers across the
+      //  chunk they are spilled, and a reload from scratch here waits for the end-of-chunk
+      //  stores in front of it)
+      int tl = tid;
+      asm volatile("" : "+v"(tl));
+      const int ek = (tl - SH_K) & (THREADS - 1), ev = (tl - SH_V) & (THREADS - 1),
+                edy = (tl - SH_DY) & (THREADS - 1), ef = (tl - SH_F) & (THREADS - 1);
       float x[8];
       if (ek < QI) {
         bf16x8_to_f32(rk, x);
@@ -291,7 +300,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         }
       }
       if (ef < CMAX) {
-        if (a.gate_alpha) rf = gate_psi(rf, a.gate_alpha[n], a.gate_beta[n]);
+        if (a.gate_alpha) rf = gate_psi(rf, g_alpha, g_beta);
         fA[ef * 4 + 0] = rf;
         fA[ef * 4 + 1] = kC * (1.f - rf);
       }
@@ -312,6 +321,10 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
     lchar *const aHw = (lchar *)lds + (rb * V + col0 + jl) * 32 + ig * 8;
     const lchar *const aHr = (lchar *)lds + rb * V * 32 + 32 * FE * ig + 8 * jl;
     if (nck > 0) stage_load(nck - 1);
+    // (waited for in front of the loop as well: a wait only on the way round the loop makes
+    //  the compiler wait at the loop head on every iteration)
+    asm volatile("" : "+v"(rk), "+v"(rv), "+v"(rdy), "+v"(rf));
+    asm volatile("" : "+v"(hck[0]), "+v"(hck[1]), "+v"(hck[2]), "+v"(hck[3]));
     for (int it = 0; it <= nck; ++it) {
       const bool active = it < nck;
       const int ck = nck - 1 - it;
@@ -393,6 +406,12 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
         }
       }
       cur = len & 1;
+      // The next chunk's prefetch (issued C steps ago) is waited for HERE, in front of the
+      // end-of-chunk global stores: the vector-memory counter is in order, so a wait placed
+      // behind the stores (where stage_store first reads the registers) would also wait
+      // until the stores have reached memory.
+      asm volatile("" : "+v"(rk), "+v"(rv), "+v"(rdy), "+v"(rf));
+      asm volatile("" : "+v"(hck[0]), "+v"(hck[1]), "+v"(hck[2]), "+v"(hck[3]));
       if (active && ct < KS) {  // dq of the chunk's last step, from the state after it
         const FragT afl = lds_ld_frag_tr<X32>(aHr + 1024 * ct, L::HX + cur * ROWS * V * 2);
         dqacc = dq_slice(dqacc, afl, len - 1);
@@ -475,9 +494,6 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   const bf16_raw *const dybase = dyg + ((size_t)b * T * N + n) * V;
   const float *const fbase = fg + (size_t)b * T * N + n;
   const uint32_t kstride = (uint32_t)a.Nqk * K, vstride = (uint32_t)N * V;
-  const int eq = (tid - SH_Q) & (THREADS - 1), ek = (tid - SH_K) & (THREADS - 1),
-            ev = (tid - SH_V) & (THREADS - 1), edy = (tid - SH_DY) & (THREADS - 1),
-            ef = (tid - SH_F) & (THREADS - 1);
   const bool wave_has_q = ((wave * 64 - SH_Q) & (THREADS - 1)) < QI;    // wave-uniform
   const bool wave_has_dy = ((wave * 64 - SH_DY) & (THREADS - 1)) < VI;
   const u4_t zero_u4 = {0u, 0u, 0u, 0u};
@@ -514,6 +530,11 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   };
   auto stage_store = [&]() {
     asm volatile("" : "+v"(rq), "+v"(rk), "+v"(rv), "+v"(rdy), "+v"(rf));
+    int tl = tid;  // (item indices rebuilt on the spot: see team A)
+    asm volatile("" : "+v"(tl));
+    const int eq = (tl - SH_Q) & (THREADS - 1), ek = (tl - SH_K) & (THREADS - 1),
+              ev = (tl - SH_V) & (THREADS - 1), edy = (tl - SH_DY) & (THREADS - 1),
+              ef = (tl - SH_F) & (THREADS - 1);
     float x[8];
     if (wave_has_q) {
       bf16x8_to_f32(rq, x);
@@ -554,7 +575,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       if (lane == 0) atomicMax(&scl[4 * set_now + 2], __builtin_bit_cast(int, md));
     }
     if (ef < CMAX) {
-      if (a.gate_alpha) rf = gate_psi(rf, a.gate_alpha[n], a.gate_beta[n]);
+      if (a.gate_alpha) rf = gate_psi(rf, g_alpha, g_beta);
       const float gm = 1.f - rf;
       const h2_t m2 = {(_Float16)(gm * (-kInvC * kInvC)), (_Float16)(gm * (-kInvC * kInvC))};
       fB[ef * 4 + 0] = rf;
@@ -564,6 +585,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
   };
 
   if (nck > 0) stage_load(nck - 1);
+  asm volatile("" : "+v"(rq), "+v"(rk), "+v"(rv), "+v"(rdy), "+v"(rf));
   for (int it = 0; it <= nck; ++it) {
     const bool active = it >= 1;
     const int ck = nck - it;
@@ -753,6 +775,8 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       // R2 of the chunk's first step; a short chunk already ran it at super-step u == len
       if (active && len == C) R2(sprev, cur ^ 1);
     }
+    // (the next chunk's prefetch is waited for in front of the end-of-chunk stores: see team A)
+    asm volatile("" : "+v"(rq), "+v"(rk), "+v"(rv), "+v"(rdy), "+v"(rf));
     {  // largest true |carry| of this wave, for the next chunk's scale
       float mc = fmaxf(fmaxf(fabsf(carry[0]), fabsf(carry[1])), fmaxf(fabsf(carry[2]), fabsf(carry[3])));
       mc = wave_max(mc) * isc;
@@ -775,8 +799,12 @@ __global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdAr
       x += __shfl_xor(x, 16, 64);
       x += __shfl_xor(x, 32, 64);
       if (ll < 16 && (int)jl2 < len) {
-        char *base = (char *)(ws.dfp + ((size_t)(part * WAVES + wave) * a.B * T + (size_t)b * T + t0) * N + n);
-        *(float *)(base + 4u * (jl2 * (uint32_t)N)) = x * (kInvC * isc);
+        // partials as [wave of the state][B][N][T]: the chunk's steps of a wave are adjacent.
+        // (In the output's own [B][T][N] order every lane writes four bytes into a line that
+        //  the workgroups of the other heads, on other XCDs, write at the same time: those
+        //  stores alone cost 7 % of the kernel.)
+        char *base = (char *)(ws.dfp + (((size_t)(part * WAVES + wave) * a.B + b) * N + n) * T + t0);
+        *(float *)(base + 4u * jl2) = x * (kInvC * isc);
       }
     }
     lds_barrier();  // E2
@@ -839,7 +867,7 @@ __global__ void bwd_parts_sum_kernel(const float *__restrict__ dvp, bf16_raw *__
                                      size_t n_dv, int P, const float *__restrict__ dfp,
                                      float *__restrict__ df, size_t n_df, int NP,
                                      const bf16_raw *__restrict__ w_r,
-                                     const bf16_raw *__restrict__ dy, int NV) {
+                                     const bf16_raw *__restrict__ dy, int NV, int T, int N) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   if (P > 1) {
     for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n_dv; e += stride) {
@@ -849,9 +877,15 @@ __global__ void bwd_parts_sum_kernel(const float *__restrict__ dvp, bf16_raw *__
       dv[e] = f32_to_bf16(s);
     }
   }
+  // df [B][T][N] from partials [NP][B][N][T]
   for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n_df; e += stride) {
-    float s = dfp[e];
-    for (int p = 1; p < NP; ++p) s += dfp[(size_t)p * n_df + e];
+    const int n = (int)(e % (size_t)N);
+    const size_t bt = e / (size_t)N;
+    const int t = (int)(bt % (size_t)T);
+    const size_t b = bt / (size_t)T;
+    const size_t src = (b * N + n) * (size_t)T + t;
+    float s = dfp[src];
+    for (int p = 1; p < NP; ++p) s += dfp[(size_t)p * n_df + src];
     df[e] = s;
   }
 }
@@ -957,7 +991,7 @@ hipError_t launch_bwd(const BwdArgs &a, hipStream_t s) {
         hipLaunchKernelGGL(bwd_parts_sum_kernel, dim3(grid_for(TL::P > 1 ? n_dv : n_df, 256)),
                            dim3(256), 0, s, (const float *)ws.dvp, (bf16_raw *)a.dv, n_dv, TL::P,
                            (const float *)ws.dfp, a.df, n_df, TL::P * TL::WAVES,
-                           (const bf16_raw *)a.w_r, (const bf16_raw *)a.dy, a.N * a.V);
+                           (const bf16_raw *)a.w_r, (const bf16_raw *)a.dy, a.N * a.V, a.T, a.N);
       }
       if (shared) {
         const size_t total = (size_t)a.B * a.T * a.Nqk * a.K;
