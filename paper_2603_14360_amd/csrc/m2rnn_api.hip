@@ -207,6 +207,11 @@ const char *m2rnn_route_string(const m2rnn_desc *desc, int bwd) {
 #undef X
     return "rowwave<?>";
   }
+  if (bwd && rowwave_bwd_supported(desc->K, desc->V)) {
+    if (desc->K == 16) return "rowwave_bwd<16,16>";
+    if (desc->K == 64) return "rowwave_bwd<64,16>";
+    return "rowwave_bwd<?>";
+  }
   const int rb = mfma_pick_rb(desc->K, desc->V, desc->B * desc->N);
 #define X(K_, V_, RB_) \
   if (desc->K == K_ && desc->V == V_ && rb == RB_) return "tile<" #K_ "," #V_ "," #RB_ ">";

@@ -83,6 +83,11 @@ size_t gate_scratch_bytes(int N);
 hipError_t gate_backward(const BwdArgs &a, hipStream_t s);
 
 // ---- matrix-core path (bf16 io, fp16 MFMA operands, fp32 state) ----
+// register-resident backward for V = 16 (one wave per 16-row block)
+bool rowwave_bwd_supported(int K, int V);
+hipError_t rowwave_bwd(const BwdArgs &a, hipStream_t s);
+size_t rowwave_bwd_workspace_bytes(int B, int T, int N, int Nqk, int K, int V);
+int rowwave_bwd_max_chunk();
 bool mfma_supported(int K, int V);
 int mfma_default_chunk(int K, int V);
 int mfma_max_chunk(int K, int V);

@@ -1019,16 +1019,39 @@ size_t ws_bytes(int B, int T, int N, int Nqk) {
 
 int mfma_pick_rb(int K, int V, int units);
 
+// epilogues shared with the register-resident backward (m2rnn_rowwave_bwd.hip)
+hipError_t bwd_sum_dW(const float *dWp, float *dW, int B, int N, int VV, int parts, hipStream_t s) {
+  hipLaunchKernelGGL(dw_parts_sum_kernel, dim3(grid_for((size_t)N * VV, 256)), dim3(256), 0, s, dWp,
+                     dW, B, N, VV, parts);
+  return hipGetLastError();
+}
+hipError_t bwd_sum_heads(const float *per_head, void *out, size_t BT, int N, int Nqk, int K,
+                         hipStream_t s) {
+  hipLaunchKernelGGL(head_sum_bf16_kernel, dim3(grid_for(BT * Nqk * K, 256)), dim3(256), 0, s,
+                     per_head, (bf16_raw *)out, BT, N, Nqk, K);
+  return hipGetLastError();
+}
+hipError_t bwd_empty(const BwdArgs &a, hipStream_t s) {
+  const size_t n_state = (size_t)a.B * a.N * a.K * a.V, n_dW = (size_t)a.N * a.V * a.V;
+  hipLaunchKernelGGL(bwd_empty_kernel, dim3(grid_for(n_state > n_dW ? n_state : n_dW, 256)),
+                     dim3(256), 0, s, a.dHT, a.dH0, n_state, a.dW, n_dW);
+  return hipGetLastError();
+}
+
 hipError_t mfma_bwd(const BwdArgs &a, hipStream_t s) {
+  // V = 16: one wave owns a row block with all its columns (no exchange, no per-step barrier)
+  if (rowwave_bwd_supported(a.K, a.V)) return rowwave_bwd(a, s);
   const int rb = mfma_pick_rb(a.K, a.V, a.B * a.N);
-#define X(K_, V_, RB_) \
-  if (a.K == K_ && a.V == V_ && rb == RB_) return launch_bwd<Tile<K_, V_, RB_>>(a, s);
+#define X(K_, V_, RB_)                                                   \
+  if constexpr (V_ != 16)                                                \
+    if (a.K == K_ && a.V == V_ && rb == RB_) return launch_bwd<Tile<K_, V_, RB_>>(a, s);
   M2RNN_TILE_CASES(X)
 #undef X
   return hipErrorInvalidValue;
 }
 
 size_t mfma_bwd_workspace_bytes(int B, int T, int N, int Nqk, int K, int V) {
+  if (rowwave_bwd_supported(K, V)) return rowwave_bwd_workspace_bytes(B, T, N, Nqk, K, V);
   const int rb = mfma_pick_rb(K, V, B * N);
 #define X(K_, V_, RB_) \
   if (K == K_ && V == V_ && rb == RB_) return ws_bytes<Tile<K_, V_, RB_>>(B, T, N, Nqk);
@@ -1038,6 +1061,7 @@ size_t mfma_bwd_workspace_bytes(int B, int T, int N, int Nqk, int K, int V) {
 }
 
 int mfma_bwd_max_chunk(int K, int V) {
+  if (rowwave_bwd_supported(K, V)) return rowwave_bwd_max_chunk();
   int best = kChunkCap;
 #define X(K_, V_, RB_) \
   if (K == K_ && V == V_) {                                                                 \

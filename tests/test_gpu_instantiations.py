@@ -20,13 +20,13 @@ CASES = [
     (32, 32, 16, 16, 0, "tile<32,32,2>", "tile<32,32,2>"),
     (32, 32, 16, 24, 4, "tile<32,32,2>", "tile<32,32,2>"),
     (32, 32, 3, 5, 0, "tile<32,32,1>", "tile<32,32,1>"),
-    (16, 16, 3, 5, 0, "tile<16,16,1>", "tile<16,16,1>"),
-    (64, 16, 3, 5, 0, "tile<64,16,1>", "tile<64,16,1>"),
+    (16, 16, 3, 5, 0, "tile<16,16,1>", "rowwave_bwd<16,16>"),
+    (64, 16, 3, 5, 0, "tile<64,16,1>", "rowwave_bwd<64,16>"),
     # one wave per row block (forward), paired with a matrix-core backward ...
     (64, 64, 32, 16, 0, "rowwave<64,64>", "tile<64,64,2>"),
     (32, 32, 32, 32, 0, "rowwave<32,32>", "tile<32,32,2>"),
-    (16, 16, 32, 64, 0, "rowwave<16,16>", "tile<16,16,1>"),
-    (64, 16, 8, 84, 1, "rowwave<64,16>", "tile<64,16,1>"),
+    (16, 16, 32, 64, 0, "rowwave<16,16>", "rowwave_bwd<16,16>"),
+    (64, 16, 8, 84, 1, "rowwave<64,16>", "rowwave_bwd<64,16>"),
     # ... or with the fp32 vector-ALU backward where no matrix-core tiling exists
     (32, 16, 2, 3, 0, "rowwave<32,16>", "generic<bf16>"),
     (128, 16, 2, 3, 0, "rowwave<128,16>", "generic<bf16>"),
