@@ -94,9 +94,9 @@ struct OvLds {
   static constexpr int PER_STEP = SLOT + VEC_A + VEC_B;
   static constexpr int FIXED = HX_BYTES + DX_BYTES + SLOT + 448;
   static constexpr int CMAX_RAW = (kLdsLimit - FIXED) / PER_STEP;
-  // per-tile cap: V = 128 stages twice the vectors per thread with a longer chunk (register
-  // spills); the one-wave teams of V = 16 lose resident workgroups to a larger LDS footprint
-  static constexpr int CCAP = V >= 128 ? 8 : (TL::THREADS <= 64 ? 12 : kChunkCap);
+  // (the one-wave teams of a V = 16 tile would lose resident workgroups to a larger LDS
+  //  footprint; those shapes are served by the register-resident backward instead)
+  static constexpr int CCAP = TL::THREADS <= 64 ? 12 : kChunkCap;
   static constexpr int CMAX = CMAX_RAW > CCAP ? CCAP : CMAX_RAW;
   static constexpr bool OK = (2 * WAVES <= 16) && (CMAX >= 4);
   static constexpr int C_ = CMAX > 0 ? CMAX : 1;
