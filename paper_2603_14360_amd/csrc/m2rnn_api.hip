@@ -33,7 +33,8 @@ m2rnn_status check_desc(const m2rnn_desc *d) {
 enum Family { kGeneric = 0, kMfma = 1, kRowWave = 2, kDecode = 3 };
 
 Family family_of(const m2rnn_desc *d) {  // backward (it owns the chunk limits)
-  if (d->io == M2RNN_BF16 && mfma_supported(d->K, d->V)) return kMfma;
+  if (d->io == M2RNN_BF16 && (mfma_supported(d->K, d->V) || rowwave_bwd_supported(d->K, d->V)))
+    return kMfma;
   return kGeneric;
 }
 
@@ -209,7 +210,9 @@ const char *m2rnn_route_string(const m2rnn_desc *desc, int bwd) {
   }
   if (bwd && rowwave_bwd_supported(desc->K, desc->V)) {
     if (desc->K == 16) return "rowwave_bwd<16,16>";
+    if (desc->K == 32) return "rowwave_bwd<32,16>";
     if (desc->K == 64) return "rowwave_bwd<64,16>";
+    if (desc->K == 128) return "rowwave_bwd<128,16>";
     return "rowwave_bwd<?>";
   }
   const int rb = mfma_pick_rb(desc->K, desc->V, desc->B * desc->N);

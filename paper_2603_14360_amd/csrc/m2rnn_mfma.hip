@@ -18,6 +18,8 @@ int mfma_default_chunk(int K, int V) { return mfma_bwd_max_chunk(K, V); }
 size_t mfma_workspace_bytes(int B, int T, int N, int Nqk, int K, int V, int C, int bwd) {
   (void)C;
   const int rb = mfma_pick_rb(K, V, B * N);
+  if (rb == 0) return bwd ? mfma_bwd_workspace_bytes(B, T, N, Nqk, K, V) : 0;  // no tiling: the
+      // register-resident kernels serve the shape (their forward needs no workspace)
   const int P = K / (16 * rb);
   const size_t fwd = P > 1 ? align256((size_t)P * B * T * N * V * 4) : 0;
   if (!bwd) return fwd;

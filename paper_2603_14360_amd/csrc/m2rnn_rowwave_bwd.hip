@@ -72,7 +72,8 @@ struct RowWaveB {
   static constexpr int OFF_PV = OFF_TR + NW * 512;      // [NW][64] f4: dv (at the end dW) partials
   static constexpr int OFF_PF = OFF_PV + NW * 1024;     // [NW][16] float: df partials
   static constexpr int BYTES = OFF_PF + NW * 64;
-  static_assert(3 * BYTES <= kLdsLimit, "three workgroups per CU");
+  // (K = 64, the paper's shape: three workgroups per CU)
+  static_assert(BYTES <= kLdsLimit && (K > 64 || 3 * BYTES <= kLdsLimit), "LDS layout");
 };
 
 __device__ __forceinline__ h4_t lds_tr16(const lchar *p, int off) {
@@ -570,7 +571,7 @@ hipError_t launch(const BwdArgs &a, hipStream_t s) {
 }  // namespace
 
 // (K, V) shapes of the register-resident backward
-#define M2RNN_ROWWAVE_BWD_CASES(X) X(16) X(64)
+#define M2RNN_ROWWAVE_BWD_CASES(X) X(16) X(32) X(64) X(128)
 
 bool rowwave_bwd_supported(int K, int V) {
   if (V != 16) return false;

@@ -27,9 +27,10 @@ CASES = [
     (32, 32, 32, 32, 0, "rowwave<32,32>", "tile<32,32,2>"),
     (16, 16, 32, 64, 0, "rowwave<16,16>", "rowwave_bwd<16,16>"),
     (64, 16, 8, 84, 1, "rowwave<64,16>", "rowwave_bwd<64,16>"),
-    # ... or with the fp32 vector-ALU backward where no matrix-core tiling exists
-    (32, 16, 2, 3, 0, "rowwave<32,16>", "generic<bf16>"),
-    (128, 16, 2, 3, 0, "rowwave<128,16>", "generic<bf16>"),
+    # ... V = 16 with any K: register-resident both ways
+    (32, 16, 2, 3, 0, "rowwave<32,16>", "rowwave_bwd<32,16>"),
+    (128, 16, 2, 3, 0, "rowwave<128,16>", "rowwave_bwd<128,16>"),
+    # ... or with the fp32 vector-ALU backward where no matrix-core backward exists
     (16, 32, 2, 3, 0, "rowwave<16,32>", "generic<bf16>"),
     (64, 32, 2, 3, 0, "rowwave<64,32>", "generic<bf16>"),
     (128, 32, 2, 3, 0, "rowwave<128,32>", "generic<bf16>"),
