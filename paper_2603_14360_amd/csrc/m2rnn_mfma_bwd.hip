@@ -907,17 +907,32 @@ __global__ void dw_parts_sum_kernel(const float *__restrict__ dWp, float *__rest
 
 __global__ void head_sum_bf16_kernel(const float *__restrict__ per_head, bf16_raw *__restrict__ out,
                                      size_t BT, int N, int Nqk, int K) {
+  // Four adjacent elements per thread (16-byte loads), and four interleaved running sums over
+  // the heads of a group (heads h, h + 4, ... each), added pairwise at the end: a fixed order
+  // that keeps four loads in flight instead of one chain of dependent loads.
   const int per = N / Nqk;
-  const size_t total = BT * Nqk * K;
+  const int K4 = K / 4;
+  const size_t total = BT * Nqk * K4;
   for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < total;
        e += (size_t)gridDim.x * blockDim.x) {
-    const int i = e % K;
-    const size_t r = e / K;
+    const int i4 = e % K4;
+    const size_t r = e / K4;
     const int g = r % Nqk;
     const size_t bt = r / Nqk;
-    float s = 0.f;
-    for (int h = 0; h < per; ++h) s += per_head[((bt * N) + g * per + h) * K + i];
-    out[e] = f32_to_bf16(s);
+    const f4_t *src = (const f4_t *)(per_head + ((bt * N) + (size_t)g * per) * K) + i4;
+    const f4_t z4 = {0.f, 0.f, 0.f, 0.f};
+    f4_t acc[4] = {z4, z4, z4, z4};
+    int h = 0;
+    for (; h + 4 <= per; h += 4) {
+      f4_t x[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) x[k] = src[(size_t)(h + k) * K4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[k] += x[k];
+    }
+    for (int k = 0; h < per; ++h, ++k) acc[k] += src[(size_t)h * K4];
+    const f4_t sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    *(uint2 *)&out[4 * e] = pack4_bf16(sum);
   }
 }
 
@@ -994,7 +1009,7 @@ hipError_t launch_bwd(const BwdArgs &a, hipStream_t s) {
                            (const bf16_raw *)a.w_r, (const bf16_raw *)a.dy, a.N * a.V, a.T, a.N);
       }
       if (shared) {
-        const size_t total = (size_t)a.B * a.T * a.Nqk * a.K;
+        const size_t total = (size_t)a.B * a.T * a.Nqk * a.K / 4;
         hipLaunchKernelGGL(head_sum_bf16_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s,
                            (const float *)ws.dqh, (bf16_raw *)a.dq, (size_t)a.B * a.T, a.N, a.Nqk,
                            a.K);
@@ -1027,7 +1042,7 @@ hipError_t bwd_sum_dW(const float *dWp, float *dW, int B, int N, int VV, int par
 }
 hipError_t bwd_sum_heads(const float *per_head, void *out, size_t BT, int N, int Nqk, int K,
                          hipStream_t s) {
-  hipLaunchKernelGGL(head_sum_bf16_kernel, dim3(grid_for(BT * Nqk * K, 256)), dim3(256), 0, s,
+  hipLaunchKernelGGL(head_sum_bf16_kernel, dim3(grid_for(BT * Nqk * K / 4, 256)), dim3(256), 0, s,
                      per_head, (bf16_raw *)out, BT, N, Nqk, K);
   return hipGetLastError();
 }
