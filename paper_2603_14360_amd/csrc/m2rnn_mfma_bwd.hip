@@ -897,11 +897,27 @@ __global__ void dw_parts_sum_kernel(const float *__restrict__ dWp, float *__rest
   for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < total;
        e += (size_t)gridDim.x * blockDim.x) {
     const int n = e / VV, r = e - (size_t)n * VV;
-    float s = 0.f;
-    for (int b = 0; b < B; ++b)
-      for (int p = 0; p < parts; ++p)
-        s += dWp[(((size_t)b * N + n) * parts + p) * VV + r];
-    dW[e] = s;
+    // (b, p) in increasing order, dealt to four running sums that are added pairwise at the
+    // end: a fixed order with four loads in flight (a single running sum is one chain of
+    // dependent loads, and this kernel is a few hundred workgroups)
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const int terms = B * parts;
+    int t = 0;
+    for (; t + 4 <= terms; t += 4) {
+      float x[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int b = (t + k) / parts, p = (t + k) - b * parts;
+        x[k] = dWp[(((size_t)b * N + n) * parts + p) * VV + r];
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[k] += x[k];
+    }
+    for (int k = 0; t < terms; ++t, ++k) {
+      const int b = t / parts, p = t - b * parts;
+      acc[k] += dWp[(((size_t)b * N + n) * parts + p) * VV + r];
+    }
+    dW[e] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
   }
 }
 
