@@ -37,10 +37,10 @@ PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9  # lane-ops per second, packed fp32 not use
 # copy).  These are figures of the profiled runs whose summaries are named here, not of the
 # run that prints them: (fetch KiB, fetch scale, write KiB, write scale, summary file).
 MEASURED_TRAFFIC = {
-    "C3": (420313, 2.000, 442656, 1.000, "profiles/c3_fwd_bwd_pmc_counters.txt"),
+    "C3": (420168, 2.000, 440213, 1.000, "profiles/c3_fwd_bwd_pmc_counters.txt"),
     "C4": (746688, 2.000, 1793306, 1.000, "profiles/c4_fwd_bwd_pmc_counters.txt"),
     "C5": (426261, 2.000, 2097664, 1.000, "profiles/c5_fwd_pmc_counters.txt"),
-    "P1": (778203, 2.000, 1551143, 1.000, "profiles/p1_fwd_bwd_pmc_counters.txt"),
+    "P1": (778174, 2.000, 1551143, 1.000, "profiles/p1_fwd_bwd_pmc_counters.txt"),
     "R1": (422375, 2.000, 502116, 1.000, "profiles/r1_fwd_bwd_pmc_counters.txt"),
 }
 

@@ -264,15 +264,25 @@ __global__ void __launch_bounds__(RW::THREADS, 3) rowwave_bwd_kernel(BwdArgs a, 
   float sc = 1.f, isc = 1.f;
   int sc_e = 0, sc_e_min = 1 << 20, mx_e_prev = -(1 << 20);
 
-  // wave-private transposition scratch: a tile written as items (row i, columns 4 g ..) at byte
-  // (4 i + g) * 8 and read at lane * 8 through the transposing load comes back with lane %
-  // 16 = column and the registers = rows 4 (lane / 16) .. + 3
-  lchar *const trw = l0 + RW::OFF_TR + rb * 512 + (jl * 4 + ig) * 8;
-  const lchar *const trr = l0 + RW::OFF_TR + rb * 512 + lane * 8;
+  // wave-private transposition scratch: a tile is written as 8-byte items (row i, columns
+  // 4 g ..); the transposing load, in which lane d of lane group G addresses item (row
+  // 4 G + d / 4, column group d % 4), returns lane % 16 = column and registers = rows
+  // 4 (lane / 16) .. + 3
+  // Where the items sit is free (every lane of the transposing load supplies its own address),
+  // so item (row i, column group g) is placed at slot 16 g + (i + 4 g) mod 16: the 64 items a
+  // wave writes (lane = (i, g)) and the 16 items a lane group of the transposing load
+  // addresses (rows 4 G .. 4 G + 3, all four column groups) then both spread evenly over the
+  // LDS banks.  (Slot 4 i + g, the plain order, made the writes 4-way bank conflicts: 40 % of
+  // the LDS-active cycles in the counters.)
+  const int slot_w = 16 * ig + ((jl + 4 * ig) & 15);                   // my own item
+  const int gs = jl & 3, is = 4 * ig + (jl >> 2);                      // the item I address when
+  const int slot_r = 16 * gs + ((is + 4 * gs) & 15);                   // reading transposed
+  lchar *const trw = l0 + RW::OFF_TR + rb * 512 + slot_w * 8;
+  const lchar *const trr = l0 + RW::OFF_TR + rb * 512 + slot_r * 8;
   // the stash of H'_{t-1} lives in LDS in the same item order: the sweep reads a step's tile
   // both ways, as written (own elements) and transposed (operand of dW)
-  lchar *const hsw = l0 + RW::OFF_HS + rb * CB * 512 + (jl * 4 + ig) * 8;
-  const lchar *const hsr = l0 + RW::OFF_HS + rb * CB * 512 + lane * 8;
+  lchar *const hsw = l0 + RW::OFF_HS + rb * CB * 512 + slot_w * 8;
+  const lchar *const hsr = l0 + RW::OFF_HS + rb * CB * 512 + slot_r * 8;
 
   if (nck > 0) stage_load(nck - 1);
   stage_wait();
