@@ -204,7 +204,7 @@ __global__ void __launch_bounds__(RW::THREADS) rowwave_fwd_kernel(FwdArgs a) {
     const bool more = blk + 1 < nblk;
     if (more) stage_load(t0 + TB);
 
-    for (int s = 0; s < len; ++s) {
+    auto step = [&](int s) __attribute__((always_inline)) {
       const int t = t0 + s;
       if (a.ckpt && t == next_ck) {  // state before step t
         float *dst = a.ckpt + ((size_t)unit * nck + ck_idx) * K * V + (size_t)row * V + 4 * ig;
@@ -281,6 +281,16 @@ __global__ void __launch_bounds__(RW::THREADS) rowwave_fwd_kernel(FwdArgs a) {
         __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);  // VALU
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
       }
+    };
+    // A full block is unrolled: the step index, and with it every LDS offset and the
+    // position of the mid-block staging, are compile-time constants (a wave issues one
+    // instruction every ~5 cycles at best: loop counters, address arithmetic and branches per
+    // step cost as much as the arithmetic).  The ragged last block runs the loop.
+    if (len == TB) {
+#pragma unroll
+      for (int s = 0; s < TB; ++s) step(s);
+    } else {
+      for (int s = 0; s < len; ++s) step(s);
     }
     lds_barrier();  // y partials of this block and the next block's staging are complete
     if (DO_Y) {
