@@ -24,7 +24,7 @@ struct Decode {
 };
 
 template <typename DC>
-__global__ void __launch_bounds__(DC::THREADS) decode_kernel(FwdArgs a) {
+__global__ void __launch_bounds__(DC::THREADS, 2) decode_kernel(FwdArgs a) {
   constexpr int K = DC::K, V = DC::V, CT = DC::CT, NW = DC::NW;
   const int unit = blockIdx.x;
   const int N = a.N;

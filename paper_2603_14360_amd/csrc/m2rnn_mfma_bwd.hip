@@ -125,7 +125,7 @@ struct OvLds {
 // [-a.clip, a.clip] as soon as it is formed (the paper's per-step clipping of the state
 // gradient); a separate instantiation, so the exact-gradient kernel pays nothing for it.
 template <typename TL, bool CLIP>
-__global__ void __launch_bounds__(2 * TL::THREADS) mfma_bwd_overlap_kernel(BwdArgs a, BwdWs ws) {
+__global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(BwdArgs a, BwdWs ws) {
   constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS, KS = TL::KS,
                 WAVES = TL::WAVES;
   constexpr int THREADS = TL::THREADS;  // per team

@@ -50,8 +50,13 @@ struct FwdSmem {
   alignas(16) f4_t yB[TL::RB][TL::CT][64];         // readout accumulators of one block
 };
 
+// (Second launch bound: at least two waves per SIMD, i.e. at most 256 registers.  With the
+//  512 that a workgroup of 256 threads or fewer may otherwise claim, the compiler puts MFMA
+//  results into accumulation registers and copies every one of them out with
+//  v_accvgpr_read before the vector ALU can use it: ten extra instructions per step on the
+//  step's critical chain.)
 template <typename TL, bool DO_Y>
-__global__ void __launch_bounds__(TL::THREADS)
+__global__ void __launch_bounds__(TL::THREADS, 2)
     mfma_fwd_kernel(FwdArgs a, float *__restrict__ ypart_ws) {
   constexpr int K = TL::K, V = TL::V, RB = TL::RB, CT = TL::CT, ROWS = TL::ROWS;
   constexpr int THREADS = TL::THREADS;

@@ -51,7 +51,7 @@ struct RowWave {
 };
 
 template <typename RW, bool DO_Y>
-__global__ void __launch_bounds__(RW::THREADS) rowwave_fwd_kernel(FwdArgs a) {
+__global__ void __launch_bounds__(RW::THREADS, 2) rowwave_fwd_kernel(FwdArgs a) {
   constexpr int K = RW::K, V = RW::V, CT = RW::CT, NW = RW::NW, THREADS = RW::THREADS;
   constexpr int NQ = (TB * K + THREADS - 1) / THREADS;
   constexpr int NV = (TB * V + THREADS - 1) / THREADS;
