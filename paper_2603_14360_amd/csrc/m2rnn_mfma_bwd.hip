@@ -68,13 +68,39 @@ __device__ __forceinline__ h4_t lds_ld_tr(const lchar *p, int off) {
   const s4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4_t *)(p + off));
   return __builtin_bit_cast(h4_t, v);
 }
+// Where the four items of a column sit inside the column's 32 bytes, and where a group of
+// four columns sits inside its 256-byte pair, is free (every lane of the transposing load
+// supplies its own address).  With SW the item (column j, rows 4 i ..) goes to
+// a = 32 j + 8 ((i + j / 4) mod 4) and then to a xor (128 if bit 8 of a is set): the items a
+// lane group reads are still 128 contiguous bytes, but the four lane groups and the two
+// halves of a k = 32 fragment start on different banks.  Measured on the backward of the
+// 128-wide tile: rotation alone 3.5 %, both 6.5 %; on the 64-wide tile neither changes the time
+// by more than its run-to-run spread, so only tiles with V > 64 use it.
+template <bool SW>
+__device__ __forceinline__ int xch_item_off(int j, int i) {
+  if constexpr (SW) {
+    const int a = 32 * j + 8 * ((i + (j >> 2)) & 3);
+    return a ^ ((a >> 1) & 128);
+  } else {
+    return 32 * j + 8 * i;
+  }
+}
+// Per-lane base offsets of a fragment read: lane (d, g) = (lane % 16, lane / 16) reads, for
+// the first half of its FE columns c0 = FE g .., item (column c0 + d / 4, rows 4 (d % 4) ..); the
+// second half (k = 32 fragments only) is the next group of 4 columns.
+template <bool X32, bool SW>
+__device__ __forceinline__ int xch_frag_off(int d, int g, int half) {
+  constexpr int FE = X32 ? 8 : 4;
+  const int c0 = FE * g + 4 * half;
+  return xch_item_off<SW>(c0 + (d >> 2), d & 3);
+}
 template <bool X32>
-__device__ __forceinline__ typename Frag<X32>::type lds_ld_frag_tr(const lchar *p, int off) {
+__device__ __forceinline__ typename Frag<X32>::type lds_ld_frag_tr(const lchar *p0, const lchar *p1, int off) {
   if constexpr (X32) {
-    const h4_t lo = lds_ld_tr(p, off), hi = lds_ld_tr(p, off + 128);
+    const h4_t lo = lds_ld_tr(p0, off), hi = lds_ld_tr(p1, off);
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   } else {
-    return lds_ld_tr(p, off);
+    return lds_ld_tr(p0, off);
   }
 }
 
@@ -318,8 +344,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
 
     // state exchange of this team: written as 8-byte items (column, rows 4 ig ..), read back
     // as row fragments through the transposing LDS load (see lds_ld_tr)
-    lchar *const aHw = (lchar *)lds + (rb * V + col0 + jl) * 32 + ig * 8;
-    const lchar *const aHr = (lchar *)lds + rb * V * 32 + 32 * FE * ig + 8 * jl;
+    lchar *const aHw = (lchar *)lds + rb * V * 32 + xch_item_off<(V > 64)>(col0 + jl, ig);
+    const lchar *const aHr0 = (lchar *)lds + rb * V * 32 + xch_frag_off<X32, (V > 64)>(jl, ig, 0);
+    const lchar *const aHr1 = (lchar *)lds + rb * V * 32 + xch_frag_off<X32, (V > 64)>(jl, ig, 1);
     if (nck > 0) stage_load(nck - 1);
     // (waited for in front of the loop as well: a wait only on the way round the loop makes
     //  the compiler wait at the loop head on every iteration)
@@ -357,7 +384,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
         FragT af[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          af[ks] = lds_ld_frag_tr<X32>(aHr, L::HX + rd * ROWS * V * 2 + 1024 * ks);
+          af[ks] = lds_ld_frag_tr<X32>(aHr0, aHr1, L::HX + rd * ROWS * V * 2 + 1024 * ks);
         const float f = fA[s * 4 + 0], gp = fA[s * 4 + 1], m2g = -2.f * gp;
         const f4_t k4 = *(const f4_t *)&kS[s * ROWS + rowb + 4 * ig];
         const float vj = (float)vS[s * V + col0 + jl];
@@ -413,7 +440,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
       asm volatile("" : "+v"(rk), "+v"(rv), "+v"(rdy), "+v"(rf));
       asm volatile("" : "+v"(hck[0]), "+v"(hck[1]), "+v"(hck[2]), "+v"(hck[3]));
       if (active && ct < KS) {  // dq of the chunk's last step, from the state after it
-        const FragT afl = lds_ld_frag_tr<X32>(aHr + 1024 * ct, L::HX + cur * ROWS * V * 2);
+        const FragT afl = lds_ld_frag_tr<X32>(aHr0 + 1024 * ct, aHr1 + 1024 * ct, L::HX + cur * ROWS * V * 2);
         dqacc = dq_slice(dqacc, afl, len - 1);
       }
       lds_barrier();  // E1: exchange buffer free, it carries the dq partials now
@@ -631,12 +658,14 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
     lchar *bR4 = l0 + (rowb + 4 * ig) * 4;                    // q rows (fp32)
     lchar *bR2 = l0 + (rowb + 4 * ig) * 2;                    // k rows (fp16)
     lchar *bC4 = l0 + (col0 + jl) * 4;                        // dy column (fp32)
-    lchar *bDw = l0 + (rb * V + col0 + jl) * 32 + ig * 8;     // dS write: item (column, rows 4 ig ..)
-    lchar *bDr = l0 + rb * V * 32 + 32 * FE * ig + 8 * jl;    // dS fragment read (transposing)
+    lchar *bDw = l0 + rb * V * 32 + xch_item_off<(V > 64)>(col0 + jl, ig);       // dS write: item (column, rows 4 ig ..)
+    lchar *bDr = l0 + rb * V * 32 + xch_frag_off<X32, (V > 64)>(jl, ig, 0);      // dS fragment read (transposing),
+    lchar *bDr1 = l0 + rb * V * 32 + xch_frag_off<X32, (V > 64)>(jl, ig, 1);     // second half of a k = 32 fragment
     lchar *bV = l0 + (FE * ig + 32 * ct) * 2;                 // v slice of the dk MFMA
     lchar *bZero = l0;                                        // wave-uniform reads (f)
     int jlB = jl;  // opaque as well: the per-step column masks (jl == s) are then built per
                    // step instead of being kept in registers for every s of an unrolled sweep
+    asm volatile("" : "+v"(bDr1));
     asm volatile("" : "+v"(bH), "+v"(bO), "+v"(bR4), "+v"(bR2), "+v"(bC4), "+v"(bDw), "+v"(bDr),
                  "+v"(bV), "+v"(bZero), "+v"(jlB));
     // The next chunk's vectors travel during this chunk.  Issued behind the set-up above: on
@@ -650,7 +679,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
       FragT af[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        af[ks] = lds_ld_frag_tr<X32>(bDr, L::DX + rd * ROWS * V * 2 + 1024 * ks);
+        af[ks] = lds_ld_frag_tr<X32>(bDr, bDr1, L::DX + rd * ROWS * V * 2 + 1024 * ks);
       f4_t d = zero4;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -757,9 +786,39 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
       dfacc = __builtin_amdgcn_mfma_f32_16x16x4f32(dfl, mine ? 1.f : 0.f, dfacc, 0, 0, 0);
       fprev = f;
     };
-    {
-      // (a fully unrolled sweep with compile-time step indices was measured 20 % slower
-      //  than this loop, unlike the recompute team's and the forward kernel's)
+    // Super-step u sweeps chunk step len - 1 - u (E1) and finishes step len - u (R2).
+    // (A fully unrolled sweep with compile-time step indices was measured 20 % slower than
+    //  a loop, unlike the recompute team's and the forward kernel's.)
+    if constexpr (V > 64) {
+      // First and last super-steps peeled: the loop between them carries no per-step
+      // conditions (11 scalar instructions per step fewer); the workgroup's barrier count
+      // per chunk stays C.  Measured 6 % on the 128-wide tile; on the 64-wide tiles the same
+      // form is 1 % SLOWER than the plain loop below, so they keep that.
+      int cur = 0, sprev = 0;
+      if (len > 0) {
+        E1(len - 1, 0);
+        sprev = len - 1;
+        cur = 1;
+      }
+      lds_barrier();
+#pragma nounroll
+      for (int u = 1; u < len; ++u) {
+        const int s = len - 1 - u;
+        R2(sprev, cur ^ 1);
+        E1(s, cur);
+        sprev = s;
+        cur ^= 1;
+        lds_barrier();
+      }
+      if (len == C) {
+        if (active) R2(sprev, cur ^ 1);
+      } else {
+        // a short chunk: its first step is finished at super-step len, the rest only keep step
+        if (len > 0) R2(sprev, cur ^ 1);
+#pragma nounroll
+        for (int u = len > 0 ? len : 1; u < C; ++u) lds_barrier();
+      }
+    } else {
       int cur = 0, sprev = 0;
 #pragma nounroll
       for (int u = 0; u < C; ++u) {
