@@ -414,9 +414,16 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
         slot[L::STASH_STEP / 8] = zp;
         lds_st<h4_t>(aHw, L::HX + wr * ROWS * V * 2, hp);
         if (s > 0 && ct < KS) {  // dq slice of the previous step; af still holds the state after it
+          if constexpr (KS > 2) {
+            // picking af[ct] out of four fragments is a ladder of branches: this wave's own
+            // fragment is read once more instead (the buffer is not rewritten before the barrier)
+            const FragT afq = lds_ld_frag_tr<X32>(aHr0 + 1024 * ct, aHr1 + 1024 * ct, L::HX + rd * ROWS * V * 2);
+            dqacc = dq_slice(dqacc, afq, s - 1);
+          } else {
 #pragma unroll
-          for (int ks = 0; ks < KS; ++ks)
-            if (ct == ks) dqacc = dq_slice(dqacc, af[ks], s - 1);
+            for (int ks = 0; ks < KS; ++ks)
+              if (ct == ks) dqacc = dq_slice(dqacc, af[ks], s - 1);
+          }
         }
       };
       if (C == CMAX) {
@@ -707,14 +714,20 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
       if (ct < KS) {
         // v_s in column sp of the B operand only: the other lanes read zeros
         const FragT bf = lds_ld<FragT>(jlB == sp ? bV + (L::VH_ + sp * V * 2) : bZero + L::ZERO_, 0);
+        if constexpr (KS > 2) {
+          // (this wave's own fragment read once more, as for dq in the recompute team)
+          const FragT afk = lds_ld_frag_tr<X32>(bDr + 1024 * ct, bDr1 + 1024 * ct, L::DX + rd * ROWS * V * 2);
+          dkacc = mfma_k32(afk, bf, dkacc);
+        } else {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          if (ct == ks) {
-            if constexpr (X32)
-              dkacc = mfma_k32(af[ks], bf, dkacc);
-            else
-              dkacc = mfma_k16(af[ks], bf, dkacc);
-          }
+          for (int ks = 0; ks < KS; ++ks)
+            if (ct == ks) {
+              if constexpr (X32)
+                dkacc = mfma_k32(af[ks], bf, dkacc);
+              else
+                dkacc = mfma_k16(af[ks], bf, dkacc);
+            }
+        }
       }
     };
     // E1 of chunk step s: G, df partial, dS into exchange buffer `wr`, row contractions
