@@ -70,29 +70,25 @@ __device__ __forceinline__ h4_t lds_ld_tr(const lchar *p, int off) {
 }
 // Where the four items of a column sit inside the column's 32 bytes, and where a group of
 // four columns sits inside its 256-byte pair, is free (every lane of the transposing load
-// supplies its own address).  With SW the item (column j, rows 4 i ..) goes to
+// supplies its own address).  Item (column j, rows 4 i ..) goes to
 // a = 32 j + 8 ((i + j / 4) mod 4) and then to a xor (128 if bit 8 of a is set): the items a
 // lane group reads are still 128 contiguous bytes, but the four lane groups and the two
-// halves of a k = 32 fragment start on different banks.  Measured on the backward of the
-// 128-wide tile: rotation alone 3.5 %, both 6.5 %; on the 64-wide tile neither changes the time
-// by more than its run-to-run spread, so only tiles with V > 64 use it.
-template <bool SW>
+// halves of a k = 32 fragment start on different banks.  In the plain order (32 j + 8 i) a
+// third of the LDS-active cycles of the backward are bank conflicts; placed like this, 1 %.
+// That is worth 6.5 % of the backward on the 128-wide tile (rotation alone 3.5 %); on the
+// 64-wide tiles, where the LDS is not what the step waits for, the time does not change.
 __device__ __forceinline__ int xch_item_off(int j, int i) {
-  if constexpr (SW) {
-    const int a = 32 * j + 8 * ((i + (j >> 2)) & 3);
-    return a ^ ((a >> 1) & 128);
-  } else {
-    return 32 * j + 8 * i;
-  }
+  const int a = 32 * j + 8 * ((i + (j >> 2)) & 3);
+  return a ^ ((a >> 1) & 128);
 }
 // Per-lane base offsets of a fragment read: lane (d, g) = (lane % 16, lane / 16) reads, for
 // the first half of its FE columns c0 = FE g .., item (column c0 + d / 4, rows 4 (d % 4) ..); the
 // second half (k = 32 fragments only) is the next group of 4 columns.
-template <bool X32, bool SW>
+template <bool X32>
 __device__ __forceinline__ int xch_frag_off(int d, int g, int half) {
   constexpr int FE = X32 ? 8 : 4;
   const int c0 = FE * g + 4 * half;
-  return xch_item_off<SW>(c0 + (d >> 2), d & 3);
+  return xch_item_off(c0 + (d >> 2), d & 3);
 }
 template <bool X32>
 __device__ __forceinline__ typename Frag<X32>::type lds_ld_frag_tr(const lchar *p0, const lchar *p1, int off) {
@@ -344,9 +340,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
 
     // state exchange of this team: written as 8-byte items (column, rows 4 ig ..), read back
     // as row fragments through the transposing LDS load (see lds_ld_tr)
-    lchar *const aHw = (lchar *)lds + rb * V * 32 + xch_item_off<(V > 64)>(col0 + jl, ig);
-    const lchar *const aHr0 = (lchar *)lds + rb * V * 32 + xch_frag_off<X32, (V > 64)>(jl, ig, 0);
-    const lchar *const aHr1 = (lchar *)lds + rb * V * 32 + xch_frag_off<X32, (V > 64)>(jl, ig, 1);
+    lchar *const aHw = (lchar *)lds + rb * V * 32 + xch_item_off(col0 + jl, ig);
+    const lchar *const aHr0 = (lchar *)lds + rb * V * 32 + xch_frag_off<X32>(jl, ig, 0);
+    const lchar *const aHr1 = (lchar *)lds + rb * V * 32 + xch_frag_off<X32>(jl, ig, 1);
     if (nck > 0) stage_load(nck - 1);
     // (waited for in front of the loop as well: a wait only on the way round the loop makes
     //  the compiler wait at the loop head on every iteration)
@@ -665,9 +661,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
     lchar *bR4 = l0 + (rowb + 4 * ig) * 4;                    // q rows (fp32)
     lchar *bR2 = l0 + (rowb + 4 * ig) * 2;                    // k rows (fp16)
     lchar *bC4 = l0 + (col0 + jl) * 4;                        // dy column (fp32)
-    lchar *bDw = l0 + rb * V * 32 + xch_item_off<(V > 64)>(col0 + jl, ig);       // dS write: item (column, rows 4 ig ..)
-    lchar *bDr = l0 + rb * V * 32 + xch_frag_off<X32, (V > 64)>(jl, ig, 0);      // dS fragment read (transposing),
-    lchar *bDr1 = l0 + rb * V * 32 + xch_frag_off<X32, (V > 64)>(jl, ig, 1);     // second half of a k = 32 fragment
+    lchar *bDw = l0 + rb * V * 32 + xch_item_off(col0 + jl, ig);       // dS write: item (column, rows 4 ig ..)
+    lchar *bDr = l0 + rb * V * 32 + xch_frag_off<X32>(jl, ig, 0);      // dS fragment read (transposing),
+    lchar *bDr1 = l0 + rb * V * 32 + xch_frag_off<X32>(jl, ig, 1);     // second half of a k = 32 fragment
     lchar *bV = l0 + (FE * ig + 32 * ct) * 2;                 // v slice of the dk MFMA
     lchar *bZero = l0;                                        // wave-uniform reads (f)
     int jlB = jl;  // opaque as well: the per-step column masks (jl == s) are then built per
