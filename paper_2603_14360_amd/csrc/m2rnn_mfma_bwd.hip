@@ -936,25 +936,49 @@ __global__ void bwd_parts_sum_kernel(const float *__restrict__ dvp, bf16_raw *__
                                      float *__restrict__ df, size_t n_df, int NP,
                                      const bf16_raw *__restrict__ w_r,
                                      const bf16_raw *__restrict__ dy, int NV, int T, int N) {
+  const size_t tid = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  if (P > 1) {
-    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n_dv; e += stride) {
-      float s = dvp[e];
-      for (int p = 1; p < P; ++p) s += dvp[(size_t)p * n_dv + e];
-      if (w_r) s = fmaf(bf16_to_f32(w_r[e % (size_t)NV]), bf16_to_f32(dy[e]), s);
-      dv[e] = f32_to_bf16(s);
+  if (P > 1) {  // four consecutive elements per thread (V is a multiple of 16)
+    for (size_t e = 4 * tid; e < n_dv; e += 4 * stride) {
+      f4_t s = *(const f4_t *)&dvp[e];
+      for (int p = 1; p < P; ++p) s += *(const f4_t *)&dvp[(size_t)p * n_dv + e];
+      if (w_r) {
+        const uint2 wv = *(const uint2 *)&w_r[e % (size_t)NV];
+        const uint2 dv2 = *(const uint2 *)&dy[e];
+        s[0] = fmaf(bf16_to_f32(wv.x & 0xFFFFu), bf16_to_f32(dv2.x & 0xFFFFu), s[0]);
+        s[1] = fmaf(bf16_to_f32(wv.x >> 16), bf16_to_f32(dv2.x >> 16), s[1]);
+        s[2] = fmaf(bf16_to_f32(wv.y & 0xFFFFu), bf16_to_f32(dv2.y & 0xFFFFu), s[2]);
+        s[3] = fmaf(bf16_to_f32(wv.y >> 16), bf16_to_f32(dv2.y >> 16), s[3]);
+      }
+      *(uint2 *)&dv[e] = pack4_bf16(s);
     }
   }
   // df [B][T][N] from partials [NP][B][N][T]
-  for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n_df; e += stride) {
-    const int n = (int)(e % (size_t)N);
-    const size_t bt = e / (size_t)N;
-    const int t = (int)(bt % (size_t)T);
-    const size_t b = bt / (size_t)T;
-    const size_t src = (b * N + n) * (size_t)T + t;
-    float s = dfp[src];
-    for (int p = 1; p < NP; ++p) s += dfp[(size_t)p * n_df + src];
-    df[e] = s;
+  if ((T & 3) == 0) {
+    // four consecutive steps of one (b, n) per thread: the partial rows are read as 16-byte
+    // pieces that consecutive lanes continue, the four results go to four rows of df
+    const size_t T4 = (size_t)T / 4;
+    for (size_t e = tid; e < n_df / 4; e += stride) {
+      const size_t bn = e / T4, t4 = e - bn * T4;
+      const size_t src = bn * (size_t)T + 4 * t4;
+      f4_t s = *(const f4_t *)&dfp[src];
+      for (int p = 1; p < NP; ++p) s += *(const f4_t *)&dfp[(size_t)p * n_df + src];
+      const size_t b = bn / (size_t)N, n = bn - b * (size_t)N;
+      float *dst = df + (b * (size_t)T + 4 * t4) * (size_t)N + n;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) dst[(size_t)r * N] = s[r];
+    }
+  } else {
+    for (size_t e = tid; e < n_df; e += stride) {
+      const int n = (int)(e % (size_t)N);
+      const size_t bt = e / (size_t)N;
+      const int t = (int)(bt % (size_t)T);
+      const size_t b = bt / (size_t)T;
+      const size_t src = (b * N + n) * (size_t)T + t;
+      float s = dfp[src];
+      for (int p = 1; p < NP; ++p) s += dfp[(size_t)p * n_df + src];
+      df[e] = s;
+    }
   }
 }
 
@@ -1087,7 +1111,7 @@ hipError_t launch_bwd(const BwdArgs &a, hipStream_t s) {
     if (a.T > 0) {
       {
         const size_t n_dv = (size_t)a.B * a.T * a.N * a.V, n_df = (size_t)a.B * a.T * a.N;
-        hipLaunchKernelGGL(bwd_parts_sum_kernel, dim3(grid_for(TL::P > 1 ? n_dv : n_df, 256)),
+        hipLaunchKernelGGL(bwd_parts_sum_kernel, dim3(grid_for((TL::P > 1 ? n_dv : n_df) / 4 + 1, 256)),
                            dim3(256), 0, s, (const float *)ws.dvp, (bf16_raw *)a.dv, n_dv, TL::P,
                            (const float *)ws.dfp, a.df, n_df, TL::P * TL::WAVES,
                            (const bf16_raw *)a.w_r, (const bf16_raw *)a.dy, a.N * a.V, a.T, a.N);
