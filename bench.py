@@ -37,11 +37,11 @@ PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9  # lane-ops per second, packed fp32 not use
 # copy).  These are figures of the profiled runs whose summaries are named here, not of the
 # run that prints them: (fetch KiB, fetch scale, write KiB, write scale, summary file).
 MEASURED_TRAFFIC = {
-    "C3": (420585, 2.000, 437748, 1.000, "profiles/c3_fwd_bwd_pmc_counters.txt"),
-    "C4": (738275, 2.000, 1356903, 1.000, "profiles/c4_fwd_bwd_pmc_counters.txt"),
+    "C3": (420591, 2.000, 437767, 1.000, "profiles/c3_fwd_bwd_pmc_counters.txt"),
+    "C4": (738301, 2.000, 1358613, 1.000, "profiles/c4_fwd_bwd_pmc_counters.txt"),
     "C5": (426252, 2.000, 2097664, 1.000, "profiles/c5_fwd_pmc_counters.txt"),
     "P1": (776987, 2.000, 1551132, 1.000, "profiles/p1_fwd_bwd_pmc_counters.txt"),
-    "R1": (424535, 2.000, 504821, 1.000, "profiles/r1_fwd_bwd_pmc_counters.txt"),
+    "R1": (424524, 2.000, 504935, 1.000, "profiles/r1_fwd_bwd_pmc_counters.txt"),
 }
 
 MFMA_PEAK = 2.5e15   # dense fp16 / bf16 flop/s
