@@ -19,6 +19,9 @@ namespace {
 constexpr int kMaxThreads = 1024;
 constexpr int kMaxPerThread = 16;  // 128*128 / 1024
 constexpr size_t kLdsBudget = 160 * 1024 - 2048;
+// unroll factor of the contraction loops: as far as the registers left by PT elements per
+// thread allow without spilling
+template <int PT> constexpr int kUnrollOf = PT <= 2 ? 8 : (PT <= 4 ? 2 : 1);
 
 template <typename IO> __device__ __forceinline__ float to_f32(IO x);
 template <> __device__ __forceinline__ float to_f32<float>(float x) { return x; }
@@ -65,17 +68,19 @@ __device__ __forceinline__ float block_sum(float x, float *red) {
 // One step of the recurrence for the elements this thread owns.  Hs holds the
 // state before the step; the new values are returned in hn[] (and Z in z[] if
 // asked) and are NOT yet written back.
-template <bool kKeepZ>
+template <bool kKeepZ, int PT>
 __device__ __forceinline__ void step_elements(const float *Hs, const float *Wf, const float *ks,
                                               const float *vs, float f, int K, int V, int KV,
                                               float *hn, float *z) {
   const int tid = threadIdx.x, nt = blockDim.x;
+  constexpr int UN = kUnrollOf<PT>;
 #pragma unroll
-  for (int m = 0; m < kMaxPerThread; ++m) {
+  for (int m = 0; m < PT; ++m) {
     const int e = tid + m * nt;
     if (e < KV) {
       const int i = e / V, j = e - i * V;
       float s = 0.f;
+#pragma unroll UN
       for (int c = 0; c < V; ++c) s = fmaf(Hs[i * V + c], Wf[c * V + j], s);
       s = fmaf(ks[i], vs[j], s);
       const float zz = tanhf(s);
@@ -85,10 +90,15 @@ __device__ __forceinline__ void step_elements(const float *Hs, const float *Wf, 
   }
 }
 
-template <typename IO>
-__global__ void __launch_bounds__(kMaxThreads) gen_fwd_kernel(FwdArgs a, const float *W32,
-                                                             int w_in_lds) {
+// PT: state (and dW) elements per thread, the smallest power of two that covers the shape:
+// the per-thread arrays and the unrolled element loops are no longer than they must be.
+// WL: W[n] is copied to LDS (it fits next to the state) and read from there; a template
+// parameter, so that every access to W has one address space (with a run-time choice the
+// contraction reads W through generic-address loads, one wait per load).
+template <typename IO, bool WL, int PT>
+__global__ void __launch_bounds__(kMaxThreads) gen_fwd_kernel(FwdArgs a, const float *W32) {
   extern __shared__ float smem[];
+  constexpr int UN = kUnrollOf<PT>;
   const int K = a.K, V = a.V, KV = K * V, T = a.T, N = a.N;
   const int tid = threadIdx.x, nt = blockDim.x;
   float *Hs = smem;
@@ -98,17 +108,16 @@ __global__ void __launch_bounds__(kMaxThreads) gen_fwd_kernel(FwdArgs a, const f
   float *Wl = vs + V;
   const int unit = blockIdx.x, b = unit / N, n = unit - b * N;
   const int g = n / (N / a.Nqk);
-  const float *Wf = W32 + (size_t)n * V * V;
-  if (w_in_lds) {
-    for (int e = tid; e < V * V; e += nt) Wl[e] = Wf[e];
-    Wf = Wl;
-  }
+  const float *Wg = W32 + (size_t)n * V * V;
+  if constexpr (WL)
+    for (int e = tid; e < V * V; e += nt) Wl[e] = Wg[e];
+  const float *Wf = WL ? Wl : Wg;
   for (int e = tid; e < KV; e += nt) Hs[e] = a.H0 ? a.H0[(size_t)unit * KV + e] : 0.f;
   __syncthreads();
   const int nck = (T + a.C - 1) / a.C;
   const IO *q = (const IO *)a.q, *k = (const IO *)a.k, *v = (const IO *)a.v;
   IO *y = (IO *)a.y;
-  float hn[kMaxPerThread];
+  float hn[PT];
   for (int t = 0; t < T; ++t) {
     if (a.ckpt && (t % a.C) == 0) {
       float *dst = a.ckpt + ((size_t)unit * nck + t / a.C) * KV;
@@ -124,10 +133,10 @@ __global__ void __launch_bounds__(kMaxThreads) gen_fwd_kernel(FwdArgs a, const f
     float f = a.f[((size_t)b * T + t) * N + n];
     if (a.gate_alpha) f = gate_psi(f, a.gate_alpha[n], a.gate_beta[n]);
     __syncthreads();
-    step_elements<false>(Hs, Wf, ks, vs, f, K, V, KV, hn, nullptr);
+    step_elements<false, PT>(Hs, Wf, ks, vs, f, K, V, KV, hn, nullptr);
     __syncthreads();
 #pragma unroll
-    for (int m = 0; m < kMaxPerThread; ++m) {
+    for (int m = 0; m < PT; ++m) {
       const int e = tid + m * nt;
       if (e < KV) Hs[e] = hn[m];
     }
@@ -135,6 +144,7 @@ __global__ void __launch_bounds__(kMaxThreads) gen_fwd_kernel(FwdArgs a, const f
     if (a.write_y) {
       for (int j = tid; j < V; j += nt) {
         float acc = 0.f;
+#pragma unroll UN
         for (int i = 0; i < K; ++i) acc = fmaf(Hs[i * V + j], qs[i], acc);
         if (a.w_r) acc = fmaf(to_f32<IO>(((const IO *)a.w_r)[n * V + j]), vs[j], acc);
         y[v_off + j] = from_f32<IO>(acc);
@@ -148,12 +158,13 @@ __global__ void __launch_bounds__(kMaxThreads) gen_fwd_kernel(FwdArgs a, const f
 
 // Backward for one (b, n): chunks from last to first; per chunk a forward
 // recompute that parks the chunk's states in `states`, then the reverse sweep.
-template <typename IO>
+template <typename IO, bool WL, int PT>
 __global__ void __launch_bounds__(kMaxThreads)
     gen_bwd_kernel(BwdArgs a, const float *W32, const float *WT32, float *states, float *dW_unit,
-                   float *dq_heads, float *dk_heads, int w_in_lds) {
+                   float *dq_heads, float *dk_heads) {
   extern __shared__ float smem[];
   __shared__ float red[kMaxThreads / 64];
+  constexpr int UN = kUnrollOf<PT>;
   const int K = a.K, V = a.V, KV = K * V, VV = V * V, T = a.T, N = a.N, C = a.C;
   const int tid = threadIdx.x, nt = blockDim.x;
   float *Hs = smem;        // state before the step
@@ -165,26 +176,25 @@ __global__ void __launch_bounds__(kMaxThreads)
   float *Wl = dys + V;
   const int unit = blockIdx.x, b = unit / N, n = unit - b * N;
   const int g = n / (N / a.Nqk);
-  const float *Wf = W32 + (size_t)n * VV;
-  const float *WTf = WT32 + (size_t)n * VV;
-  if (w_in_lds) {
+  const float *Wg = W32 + (size_t)n * VV;
+  const float *WTg = WT32 + (size_t)n * VV;
+  if constexpr (WL)
     for (int e = tid; e < VV; e += nt) {
-      Wl[e] = Wf[e];
-      Wl[VV + e] = WTf[e];
+      Wl[e] = Wg[e];
+      Wl[VV + e] = WTg[e];
     }
-    Wf = Wl;
-    WTf = Wl + VV;
-  }
+  const float *Wf = WL ? Wl : Wg;
+  const float *WTf = WL ? Wl + VV : WTg;
   const IO *q = (const IO *)a.q, *k = (const IO *)a.k, *v = (const IO *)a.v,
            *dy = (const IO *)a.dy;
   float *st = states + (size_t)unit * (C + 1) * KV;
   const int nck = (T + C - 1) / C;
 
-  float carry[kMaxPerThread];  // dL/dH flowing from later steps, per owned element
-  float dWacc[kMaxPerThread];  // this thread's elements of dW (indexed over V*V)
-  float hn[kMaxPerThread], z[kMaxPerThread];
+  float carry[PT];  // dL/dH flowing from later steps, per owned element
+  float dWacc[PT];  // this thread's elements of dW (indexed over V*V)
+  float hn[PT], z[PT];
 #pragma unroll
-  for (int m = 0; m < kMaxPerThread; ++m) {
+  for (int m = 0; m < PT; ++m) {
     const int e = tid + m * nt;
     carry[m] = (e < KV && a.dHT) ? a.dHT[(size_t)unit * KV + e] : 0.f;
     dWacc[m] = 0.f;
@@ -210,10 +220,10 @@ __global__ void __launch_bounds__(kMaxThreads)
       float f = a.f[((size_t)b * T + t) * N + n];
     if (a.gate_alpha) f = gate_psi(f, a.gate_alpha[n], a.gate_beta[n]);
       __syncthreads();
-      step_elements<false>(Hs, Wf, ks, vs, f, K, V, KV, hn, nullptr);
+      step_elements<false, PT>(Hs, Wf, ks, vs, f, K, V, KV, hn, nullptr);
       __syncthreads();
 #pragma unroll
-      for (int m = 0; m < kMaxPerThread; ++m) {
+      for (int m = 0; m < PT; ++m) {
         const int e = tid + m * nt;
         if (e < KV) Hs[e] = hn[m];
       }
@@ -237,9 +247,9 @@ __global__ void __launch_bounds__(kMaxThreads)
     if (a.gate_alpha) f = gate_psi(f, a.gate_alpha[n], a.gate_beta[n]);
       __syncthreads();
       // recompute Z_t and H_t exactly as the forward did
-      step_elements<true>(Hs, Wf, ks, vs, f, K, V, KV, hn, z);
+      step_elements<true, PT>(Hs, Wf, ks, vs, f, K, V, KV, hn, z);
 #pragma unroll
-      for (int m = 0; m < kMaxPerThread; ++m) {
+      for (int m = 0; m < PT; ++m) {
         const int e = tid + m * nt;
         if (e < KV) Xs[e] = hn[m];
       }
@@ -247,6 +257,7 @@ __global__ void __launch_bounds__(kMaxThreads)
       // dq_t = H_t dy_t
       for (int i = tid; i < K; i += nt) {
         float acc = 0.f;
+#pragma unroll UN
         for (int j = 0; j < V; ++j) acc = fmaf(Xs[i * V + j], dys[j], acc);
         if (dq_heads)
           dq_heads[(((size_t)b * T + t) * N + n) * K + i] = acc;
@@ -257,7 +268,7 @@ __global__ void __launch_bounds__(kMaxThreads)
       // G = q dy^T + carry ; df ; dS = (1-f) G (1 - Z^2)
       float dfp = 0.f;
 #pragma unroll
-      for (int m = 0; m < kMaxPerThread; ++m) {
+      for (int m = 0; m < PT; ++m) {
         const int e = tid + m * nt;
         if (e < KV) {
           const int i = e / V, j = e - i * V;
@@ -271,11 +282,12 @@ __global__ void __launch_bounds__(kMaxThreads)
       if (tid == 0) a.df[((size_t)b * T + t) * N + n] = dft;
       // carry = f G + dS W^T
 #pragma unroll
-      for (int m = 0; m < kMaxPerThread; ++m) {
+      for (int m = 0; m < PT; ++m) {
         const int e = tid + m * nt;
         if (e < KV) {
           const int i = e / V, c = e - i * V;
           float acc = 0.f;
+#pragma unroll UN
           for (int j = 0; j < V; ++j) acc = fmaf(Xs[i * V + j], WTf[j * V + c], acc);
           carry[m] = fmaf(f, carry[m], acc);
           if (a.clip > 0.f) carry[m] = fminf(fmaxf(carry[m], -a.clip), a.clip);
@@ -283,11 +295,12 @@ __global__ void __launch_bounds__(kMaxThreads)
       }
       // dW += H_{t-1}^T dS
 #pragma unroll
-      for (int m = 0; m < kMaxPerThread; ++m) {
+      for (int m = 0; m < PT; ++m) {
         const int e = tid + m * nt;
         if (e < VV) {
           const int c = e / V, j = e - c * V;
           float acc = 0.f;
+#pragma unroll UN
           for (int i = 0; i < K; ++i) acc = fmaf(Hs[i * V + c], Xs[i * V + j], acc);
           dWacc[m] += acc;
         }
@@ -295,6 +308,7 @@ __global__ void __launch_bounds__(kMaxThreads)
       // dk_t = dS v_t ; dv_t = dS^T k_t
       for (int i = tid; i < K; i += nt) {
         float acc = 0.f;
+#pragma unroll UN
         for (int j = 0; j < V; ++j) acc = fmaf(Xs[i * V + j], vs[j], acc);
         if (dk_heads)
           dk_heads[(((size_t)b * T + t) * N + n) * K + i] = acc;
@@ -303,6 +317,7 @@ __global__ void __launch_bounds__(kMaxThreads)
       }
       for (int j = tid; j < V; j += nt) {
         float acc = 0.f;
+#pragma unroll UN
         for (int i = 0; i < K; ++i) acc = fmaf(Xs[i * V + j], ks[i], acc);
         if (a.w_r) acc = fmaf(to_f32<IO>(((const IO *)a.w_r)[n * V + j]), dys[j], acc);
         ((IO *)a.dv)[v_off + j] = from_f32<IO>(acc);
@@ -311,7 +326,7 @@ __global__ void __launch_bounds__(kMaxThreads)
     }
   }
 #pragma unroll
-  for (int m = 0; m < kMaxPerThread; ++m) {
+  for (int m = 0; m < PT; ++m) {
     const int e = tid + m * nt;
     if (e < KV && a.dH0) a.dH0[(size_t)unit * KV + e] = carry[m];
     if (e < VV) dW_unit[(size_t)unit * VV + e] = dWacc[m];
@@ -371,7 +386,7 @@ __global__ void head_group_sum_kernel(const float *per_head, IO *out, size_t BT,
 }
 
 struct GenericPlan {
-  int threads;
+  int threads, per_thread;
   size_t lds_fwd, lds_bwd;
   int w_lds_fwd, w_lds_bwd;
 };
@@ -382,6 +397,9 @@ GenericPlan make_plan(int K, int V) {
   p.threads = KV < kMaxThreads ? KV : kMaxThreads;
   // every thread must be able to own its share of dW (V*V elements) as well
   while (p.threads < kMaxThreads && VV > p.threads * kMaxPerThread) p.threads *= 2;
+  const int big = KV > VV ? KV : VV;
+  p.per_thread = 1;
+  while (p.per_thread * p.threads < big) p.per_thread *= 2;
   const size_t base_f = (size_t)(KV + 2 * K + V) * 4;
   p.w_lds_fwd = base_f + (size_t)VV * 4 <= kLdsBudget;
   p.lds_fwd = base_f + (p.w_lds_fwd ? (size_t)VV * 4 : 0);
@@ -430,11 +448,18 @@ hipError_t run_fwd(const FwdArgs &a, hipStream_t s) {
                      s, (const IO *)a.W, W32, WT32, a.N, a.V);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = set_max_lds_once(gen_fwd_kernel<IO>, (int)kLdsBudget);  // (the need varies with the shape)
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(gen_fwd_kernel<IO>, dim3(units), dim3(p.threads), p.lds_fwd, s, a,
-                     (const float *)W32, p.w_lds_fwd);
-  return hipGetLastError();
+  auto go = [&](auto kernel) {
+    hipError_t e2 = set_max_lds_once(kernel, (int)kLdsBudget);  // (the need varies with the shape)
+    if (e2 != hipSuccess) return e2;
+    hipLaunchKernelGGL(kernel, dim3(units), dim3(p.threads), p.lds_fwd, s, a, (const float *)W32);
+    return hipGetLastError();
+  };
+#define M2RNN_GEN_FWD(PT_) \
+  if (p.per_thread == PT_)  \
+    return p.w_lds_fwd ? go(gen_fwd_kernel<IO, true, PT_>) : go(gen_fwd_kernel<IO, false, PT_>);
+  M2RNN_GEN_FWD(1) M2RNN_GEN_FWD(2) M2RNN_GEN_FWD(4) M2RNN_GEN_FWD(8) M2RNN_GEN_FWD(16)
+#undef M2RNN_GEN_FWD
+  return hipErrorInvalidValue;
 }
 
 template <typename IO>
@@ -454,12 +479,20 @@ hipError_t run_bwd(const BwdArgs &a, hipStream_t s) {
     hipLaunchKernelGGL(w_prep_kernel<IO>, dim3(grid_for((size_t)a.N * a.V * a.V, 256)), dim3(256),
                        0, s, (const IO *)a.W, W32, WT32, a.N, a.V);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    e = set_max_lds_once(gen_bwd_kernel<IO>, (int)kLdsBudget);
+    auto go = [&](auto kernel) {
+      hipError_t e2 = set_max_lds_once(kernel, (int)kLdsBudget);
+      if (e2 != hipSuccess) return e2;
+      hipLaunchKernelGGL(kernel, dim3(units), dim3(p.threads), p.lds_bwd, s, a, (const float *)W32,
+                         (const float *)WT32, states, dW_unit, dq_heads, dk_heads);
+      return hipGetLastError();
+    };
+    e = hipErrorInvalidValue;
+#define M2RNN_GEN_BWD(PT_) \
+  if (p.per_thread == PT_)  \
+    e = p.w_lds_bwd ? go(gen_bwd_kernel<IO, true, PT_>) : go(gen_bwd_kernel<IO, false, PT_>);
+    M2RNN_GEN_BWD(1) M2RNN_GEN_BWD(2) M2RNN_GEN_BWD(4) M2RNN_GEN_BWD(8) M2RNN_GEN_BWD(16)
+#undef M2RNN_GEN_BWD
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(gen_bwd_kernel<IO>, dim3(units), dim3(p.threads), p.lds_bwd, s, a,
-                       (const float *)W32, (const float *)WT32, states, dW_unit, dq_heads,
-                       dk_heads, p.w_lds_bwd);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
     if (shared && a.T > 0) {
       const size_t total = (size_t)a.B * a.T * a.Nqk * a.K;
       hipLaunchKernelGGL(head_group_sum_kernel<IO>, dim3(grid_for(total, 256)), dim3(256), 0, s,

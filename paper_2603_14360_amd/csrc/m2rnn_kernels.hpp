@@ -43,19 +43,42 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Raises a kernel's dynamic-LDS limit the first time the kernel is launched on a device,
 // not on every call (the entry points are otherwise launch-only, and a decode loop pays host
-// latency for every extra runtime call).  One instance per kernel: `Tag` is the kernel's
-// own type.  `bytes` must not depend on the call.
-template <typename Tag>
-inline hipError_t set_max_lds_once(Tag kernel, int bytes) {
-  static std::atomic<uint64_t> done{0};
+// latency for every extra runtime call).  Kernels are told apart by their address (the
+// instantiations of a kernel template share one function type, so a flag per type would
+// be set by the first of them for all): a small open-addressing table of (kernel, devices
+// done), lock-free; when it is full the attribute is simply set on every call.  `bytes`
+// must not depend on the call.
+inline hipError_t set_max_lds_once_addr(const void *kernel, int bytes) {
+  struct Slot {
+    std::atomic<const void *> fn{nullptr};
+    std::atomic<uint64_t> done{0};
+  };
+  constexpr unsigned kSlots = 512;
+  static Slot slots[kSlots];
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   const uint64_t bit = 1ull << (dev & 63);
-  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
-  e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
-  return e;
+  unsigned h = (unsigned)((reinterpret_cast<uintptr_t>(kernel) >> 4) % kSlots);
+  for (unsigned probe = 0; probe < kSlots; ++probe, h = (h + 1) % kSlots) {
+    const void *cur = slots[h].fn.load(std::memory_order_acquire);
+    if (cur == nullptr) {
+      const void *expected = nullptr;
+      cur = slots[h].fn.compare_exchange_strong(expected, kernel, std::memory_order_acq_rel)
+                ? kernel
+                : expected;
+    }
+    if (cur != kernel) continue;
+    if (slots[h].done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) slots[h].done.fetch_or(bit, std::memory_order_release);
+    return e;
+  }
+  return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+template <typename Fn>
+inline hipError_t set_max_lds_once(Fn kernel, int bytes) {
+  return set_max_lds_once_addr((const void *)kernel, bytes);
 }
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 

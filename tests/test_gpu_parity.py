@@ -38,6 +38,9 @@ SHAPES = [
     ("f32", 1, 21, 1, 128, 128, 0),
     ("f32", 2, 40, 4, 32, 32, 1),
     ("f32", 1, 40, 6, 32, 16, 2),
+    ("f32", 1, 19, 2, 64, 32, 0),    # fp32 kernels with 2 state elements per thread
+    ("f32", 1, 18, 2, 64, 64, 0),    # ... 4
+    ("f32", 1, 17, 1, 128, 64, 0),   # ... 8 (16: the 128 x 128 case above)
     ("bf16", 2, 37, 3, 16, 16, 0),
     ("bf16", 2, 70, 2, 32, 32, 0),
     ("bf16", 2, 100, 3, 64, 64, 0),
