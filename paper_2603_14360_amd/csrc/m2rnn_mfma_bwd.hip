@@ -100,6 +100,14 @@ __device__ __forceinline__ typename Frag<X32>::type lds_ld_frag_tr(const lchar *
   }
 }
 
+// The lane index computed on the spot (two instructions).  The chunk-boundary code derives
+// its per-lane offsets from this instead of from a lane index kept in a register since the
+// kernel's start: on the tiles at the register limit that register is spilled, and a reload
+// from scratch in the boundary code waits for every global store issued before it.
+__device__ __forceinline__ int lane_now() {
+  return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+
 template <typename TL>
 struct OvLds {
   static constexpr int ROWS = TL::ROWS, V = TL::V, RB = TL::RB, CT = TL::CT,
@@ -242,7 +250,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
     auto stage_load = [&](int ck) {
       const int t0 = ck * C;
       const int len = (T - t0) < C ? (T - t0) : C;
-      int tl = tid;
+      int tl = wave * 64 + lane_now();
       asm volatile("" : "+v"(tl));
       {
         const int e = (tl - SH_K) & (THREADS - 1), s = e / RL, p = e - s * RL;
@@ -278,7 +286,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
       // (item indices rebuilt from the thread index on the spot: kept in registers across the
       //  chunk they are spilled, and a reload from scratch here waits for the end-of-chunk
       //  stores in front of it)
-      int tl = tid;
+      int tl = wave * 64 + lane_now();
       asm volatile("" : "+v"(tl));
       const int ek = (tl - SH_K) & (THREADS - 1), ev = (tl - SH_V) & (THREADS - 1),
                 edy = (tl - SH_DY) & (THREADS - 1), ef = (tl - SH_F) & (THREADS - 1);
@@ -458,7 +466,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
           d += fin[(rb * KS + ks) * 64 + lane] * fA[jl * 4 + 2 + (32 * ks) / 64];
         d *= kInvC;
         // (uniform base + 32-bit byte offset rebuilt from the lane index: see stage_load)
-        int ll = lane;
+        int ll = lane_now();
         asm volatile("" : "+v"(ll));
         const uint32_t jl2 = ll & 15, ig2 = ll >> 4;
         if (ws.dqh) {
@@ -530,7 +538,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
   auto stage_load = [&](int ck) {  // (addresses as in team A)
     const int t0 = ck * C;
     const int len = (T - t0) < C ? (T - t0) : C;
-    int tl = tid;
+    int tl = wave * 64 + lane_now();
     asm volatile("" : "+v"(tl));
     {
       const int e = (tl - SH_Q) & (THREADS - 1), s = e / RL, p = e - s * RL;
@@ -560,7 +568,7 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
   };
   auto stage_store = [&]() {
     asm volatile("" : "+v"(rq), "+v"(rk), "+v"(rv), "+v"(rdy), "+v"(rf));
-    int tl = tid;  // (item indices rebuilt on the spot: see team A)
+    int tl = wave * 64 + lane_now();  // (item indices rebuilt on the spot: see team A)
     asm volatile("" : "+v"(tl));
     const int eq = (tl - SH_Q) & (THREADS - 1), ek = (tl - SH_K) & (THREADS - 1),
               ev = (tl - SH_V) & (THREADS - 1), edy = (tl - SH_DY) & (THREADS - 1),
@@ -857,12 +865,12 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
     // Store addresses below: wave-uniform 64-bit base + 32-bit byte offset rebuilt from the
     // lane index on the spot.  Kept in registers over the chunk they would be spilled, and a
     // reload from scratch in front of a store waits for every store issued before it.
-    int ll = lane;
+    int ll = lane_now();
     asm volatile("" : "+v"(ll));
     const uint32_t jl2 = ll & 15, ig2 = ll >> 4;
     if (active) {
-      if (ct < KS) fink[(rb * KS + ct) * 64 + lane] = dkacc * isc;
-      finv[wave * 64 + lane] = dvacc * isc;
+      if (ct < KS) fink[(rb * KS + ct) * 64 + ll] = dkacc * isc;
+      finv[wave * 64 + ll] = dvacc * isc;
       float x = (dfacc[0] + dfacc[1]) + (dfacc[2] + dfacc[3]);
       x += __shfl_xor(x, 16, 64);
       x += __shfl_xor(x, 32, 64);
@@ -878,9 +886,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
     lds_barrier();  // E2
     if (active) {
       if (ct == 0 && (int)jl2 < len) {
-        f4_t d = fink[(rb * KS + 0) * 64 + lane];
+        f4_t d = fink[(rb * KS + 0) * 64 + ll];
 #pragma unroll
-        for (int ks = 1; ks < KS; ++ks) d += fink[(rb * KS + ks) * 64 + lane];
+        for (int ks = 1; ks < KS; ++ks) d += fink[(rb * KS + ks) * 64 + ll];
         if (ws.dkh) {
           char *base = (char *)(ws.dkh + (((size_t)b * T + t0) * N + n) * K + row_base + rowb);
           *(f4_t *)(base + 4u * (jl2 * (uint32_t)(N * K) + 4u * ig2)) = d;
@@ -890,9 +898,9 @@ __global__ void __launch_bounds__(2 * TL::THREADS, 2) mfma_bwd_overlap_kernel(Bw
         }
       }
       if (rb == 0) {
-        f4_t d = finv[(0 * CT + ct) * 64 + lane];
+        f4_t d = finv[(0 * CT + ct) * 64 + ll];
 #pragma unroll
-        for (int r2 = 1; r2 < RB; ++r2) d += finv[(r2 * CT + ct) * 64 + lane];
+        for (int r2 = 1; r2 < RB; ++r2) d += finv[(r2 * CT + ct) * 64 + ll];
         const size_t row0 = (((size_t)b * T + t0) * N + n) * V + col0;  // uniform: step t0, column col0
         const uint32_t eoff = 4u * ig2 * vstride + jl2;                 // element offset of (step 4 ig, column jl)
 #pragma unroll
